@@ -1,0 +1,166 @@
+"""Layout oracle for hierarchical ZeRO sharding (test infrastructure, not product).
+
+Plain Python integers, no numpy, no blocking: every quantity is written out the
+way the method defines it so it can be checked by eye.
+
+What the paper fixes (Section 4.1.1, Table 1 and the M_hzp equation):
+  * five per-parameter arrays: bf16 parameters (2 B), fp32 gradients (4 B),
+    fp32 master copy, momentum and variance (4 B each, 12 B together);
+  * three independent sharding-group sizes.  The M_hzp equation divides the
+    12 B of optimizer state by Z1, the 4 B gradient by Z2 and the 2 B
+    parameter by Z3, and the experiments use Z1=64, Z2=Z3=8 (Table 2), so
+    Z_k is the group of ZeRO *stage* k: Z1 optimizer states, Z2 gradients,
+    Z3 parameters.  (The sentence introducing the symbols lists them in the
+    opposite order; the equation, Figure 1 and the experiments agree with the
+    reading used here.)
+  * parameters and gradients are sharded inside a small (intra-node) group and
+    optimizer states inside a larger one (Section 3.1, Figure 1).
+
+What the paper leaves open and this oracle fixes (each is a stated reading):
+  * one flat bucket per (layer, dtype class); every tensor starts on a multiple
+    of A elements; the bucket is zero-padded to a multiple of A*Z1;
+  * Z3 divides Z1 (true of every configuration the paper reports) and Z2 is
+    Z3;  K = Z1 / Z3;
+  * rank rho in [0, Z1): ZeRO-3 index j = rho mod Z3 (consecutive ranks form
+    the parameter group, i.e. it sits inside a node), outer index
+    k = rho div Z3, ZeRO-1 shard i = j*K + k, so ZeRO-1 shard i lies inside
+    ZeRO-3 shard j and the post-step gather (Section 4.1.2, "Optimizer Step")
+    is a contiguous concatenation.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this.
+"""
+
+CLASS_BF16 = 0
+CLASS_F32 = 1
+_ELEM_BYTES = {CLASS_BF16: 2, CLASS_F32: 4}
+
+
+def round_up(x, q):
+    return ((x + q - 1) // q) * q
+
+
+def is_pow2(x):
+    return x >= 1 and (x & (x - 1)) == 0
+
+
+class PlanError(ValueError):
+    pass
+
+
+def make_plan(tensors_per_layer, tensor_numel, align, z3, z1, z2=0,
+              tensor_class=None, tensor_wd_mult=None):
+    """Return the layout as a dict of plain lists/ints.
+
+    tensors_per_layer : list of ints, one per layer, each >= 1
+    tensor_numel      : flat list of element counts, layer after layer, each >= 1
+    tensor_class      : None (all bf16) or flat list of 0/1
+    tensor_wd_mult    : None (all 1.0) or flat list of floats
+    """
+    n_layers = len(tensors_per_layer)
+    n_tensors = sum(tensors_per_layer)
+    if n_layers < 1 or any(t < 1 for t in tensors_per_layer):
+        raise PlanError("every layer needs at least one tensor")
+    if len(tensor_numel) != n_tensors or any(n < 1 for n in tensor_numel):
+        raise PlanError("tensor_numel must hold one positive count per tensor")
+    if not is_pow2(align) or align < 8:
+        raise PlanError("alignment must be a power of two >= 8")
+    if z3 < 1 or z1 < 1 or z1 % z3 != 0:
+        raise PlanError("need Z3 >= 1 and Z3 | Z1")
+    if z2 not in (0, z3):
+        raise PlanError("Z2 must equal Z3 (0 means: same as Z3)")
+    if tensor_class is None:
+        tensor_class = [CLASS_BF16] * n_tensors
+    if tensor_wd_mult is None:
+        tensor_wd_mult = [1.0] * n_tensors
+    if any(c not in (CLASS_BF16, CLASS_F32) for c in tensor_class):
+        raise PlanError("unknown tensor class")
+
+    K = z1 // z3
+    buckets = []          # in (layer, class) order
+    tensors = [None] * n_tensors
+    base = 0
+    tid0 = 0
+    for layer in range(n_layers):
+        ids = list(range(tid0, tid0 + tensors_per_layer[layer]))
+        tid0 += tensors_per_layer[layer]
+        for cls in (CLASS_BF16, CLASS_F32):
+            members = [t for t in ids if tensor_class[t] == cls]
+            if not members:
+                continue                       # a bucket with no tensor does not exist
+            off = 0
+            payload_end = 0
+            for t in members:                  # given order, each start A-aligned
+                tensors[t] = dict(id=t, layer=layer, cls=cls, offset=off,
+                                  numel=tensor_numel[t], wd_mult=tensor_wd_mult[t],
+                                  bucket=len(buckets))
+                payload_end = off + tensor_numel[t]
+                off = round_up(payload_end, align)
+            P = round_up(payload_end, align * z1)
+            buckets.append(dict(layer=layer, cls=cls, tensor_ids=members,
+                                payload_end=payload_end, P=P,
+                                S3=P // z3, S1=P // z1, base=base))
+            base += P
+    return dict(align=align, z3=z3, z2=z3, z1=z1, K=K, n_layers=n_layers,
+                buckets=buckets, tensors=tensors, total_padded=base)
+
+
+def find_bucket(plan, layer, cls):
+    for b in plan["buckets"]:
+        if b["layer"] == layer and b["cls"] == cls:
+            return b
+    return None
+
+
+def rank_to_indices(plan, rank):
+    """rank -> (j, k, i): ZeRO-3 index, outer index, ZeRO-1 shard index."""
+    z3, z1, K = plan["z3"], plan["z1"], plan["K"]
+    if not (0 <= rank < z1):
+        raise PlanError("rank out of range")
+    j = rank % z3
+    k = rank // z3
+    return j, k, j * K + k
+
+
+def shard_range(plan, bucket, level, rank):
+    """(begin, length) in bucket-relative elements of the rank's shard.
+
+    level 3: the parameter/gradient shard (group size Z3);
+    level 1: the optimizer-state shard (group size Z1).
+    """
+    j, k, i = rank_to_indices(plan, rank)
+    if level == 3:
+        return j * bucket["S3"], bucket["S3"]
+    if level == 1:
+        return i * bucket["S1"], bucket["S1"]
+    raise PlanError("level must be 1 or 3")
+
+
+def per_rank_bytes(plan):
+    """(optimizer, gradient, parameter) bytes one rank holds.
+
+    Table 1 with N replaced by the padded length of each bucket: 12 B of
+    fp32 master/momentum/variance per ZeRO-1 element, a 4 B fp32 gradient per
+    gradient-shard element, and the parameter itself (2 B bf16; 4 B for the
+    fp32 class) per ZeRO-3 element.
+    """
+    opt = grad = par = 0
+    for b in plan["buckets"]:
+        opt += 12 * b["S1"]
+        grad += 4 * (b["P"] // plan["z2"])
+        par += _ELEM_BYTES[b["cls"]] * b["S3"]
+    return opt, grad, par
+
+
+def hzp_memory_bytes(N, z1, z2, z3):
+    """M_hzp of Section 4.1.1 as an exact fraction (numerator, denominator)."""
+    from fractions import Fraction
+    return Fraction(12 * N, z1) + Fraction(4 * N, z2) + Fraction(2 * N, z3)
+
+
+def owner_tensor(plan, bucket, pos):
+    """Tensor id that owns bucket element `pos`, or -1 for padding (linear scan)."""
+    for t in bucket["tensor_ids"]:
+        rec = plan["tensors"][t]
+        if rec["offset"] <= pos < rec["offset"] + rec["numel"]:
+            return t
+    return -1

@@ -1,0 +1,221 @@
+"""Pins for the layout oracle: brute-force ownership enumeration, invariants on random
+descriptors, the paper's closed-form memory model, special cases and hand-worked values."""
+import os
+from fractions import Fraction
+
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import hzp_inputs
+from oracle import planner as op
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                yield line.split()
+
+
+@st.composite
+def descriptors(draw, max_numel=300):
+    n_layers = draw(st.integers(1, 4))
+    tpl = [draw(st.integers(1, 5)) for _ in range(n_layers)]
+    n = sum(tpl)
+    numel = [draw(st.integers(1, max_numel)) for _ in range(n)]
+    cls = draw(st.one_of(st.none(), st.lists(st.integers(0, 1), min_size=n, max_size=n)))
+    align = draw(st.sampled_from([8, 16, 32, 128]))
+    z3 = draw(st.sampled_from([1, 2, 3, 4, 8]))
+    K = draw(st.sampled_from([1, 2, 4, 5]))
+    return dict(tensors_per_layer=tpl, tensor_numel=numel, tensor_class=cls,
+                align=align, z3=z3, z1=z3 * K)
+
+
+# ------------------------------------------------------------------ brute force ownership
+
+@settings(max_examples=60, deadline=None)
+@given(descriptors())
+def test_every_element_owned_exactly_once(d):
+    """Enumerate every bucket position; count the shards that contain it at each level."""
+    plan = op.make_plan(**d)
+    z3, z1, K = plan["z3"], plan["z1"], plan["K"]
+    seen_i = set()
+    for rank in range(z1):
+        j, k, i = op.rank_to_indices(plan, rank)
+        assert 0 <= j < z3 and 0 <= k < K and 0 <= i < z1
+        seen_i.add(i)
+    assert seen_i == set(range(z1))                       # rank -> ZeRO-1 shard is a bijection
+    for b in plan["buckets"]:
+        own3 = [0] * b["P"]
+        own1 = [0] * b["P"]
+        for rank in range(z1):
+            j, k, i = op.rank_to_indices(plan, rank)
+            b3, l3 = op.shard_range(plan, b, 3, rank)
+            b1, l1 = op.shard_range(plan, b, 1, rank)
+            assert b3 <= b1 and b1 + l1 <= b3 + l3          # ZeRO-1 shard nests in the ZeRO-3 shard
+            assert i // K == j
+            for x in range(b1, b1 + l1):
+                own1[x] += 1
+            if k == 0:                                      # one representative per ZeRO-3 shard
+                for x in range(b3, b3 + l3):
+                    own3[x] += 1
+        assert own1 == [1] * b["P"]
+        assert own3 == [1] * b["P"]
+        # the K ranks sharing ZeRO-3 index j tile that shard, in k order
+        for j in range(z3):
+            pieces = sorted(op.shard_range(plan, b, 1, j + z3 * k)[0] for k in range(K))
+            assert pieces == [j * b["S3"] + k * b["S1"] for k in range(K)]
+
+
+@settings(max_examples=100, deadline=None)
+@given(descriptors(max_numel=5000))
+def test_layout_invariants(d):
+    plan = op.make_plan(**d)
+    A, z3, z1 = plan["align"], plan["z3"], plan["z1"]
+    base = 0
+    n_seen = 0
+    for b in plan["buckets"]:
+        assert b["base"] == base
+        base += b["P"]
+        prev_end = 0
+        for t in b["tensor_ids"]:
+            rec = plan["tensors"][t]
+            assert rec["offset"] % A == 0
+            assert rec["offset"] >= prev_end                 # disjoint, in the given order
+            assert rec["offset"] - prev_end < A              # no more than alignment padding
+            prev_end = rec["offset"] + rec["numel"]
+            assert rec["layer"] == b["layer"] and rec["cls"] == b["cls"]
+            n_seen += 1
+        assert b["tensor_ids"] == sorted(b["tensor_ids"])
+        assert b["payload_end"] == prev_end
+        assert b["payload_end"] <= b["P"] < b["payload_end"] + A * z1
+        assert b["P"] % (A * z1) == 0
+        assert b["S1"] * z1 == b["P"] == b["S3"] * z3
+        assert b["S1"] % A == 0 and b["S3"] % A == 0
+        # every A-block meets at most one tensor
+        for blk in range(b["P"] // A):
+            owners = {op.owner_tensor(plan, b, x) for x in range(blk * A, (blk + 1) * A)} - {-1}
+            assert len(owners) <= 1
+    assert n_seen == len(plan["tensors"])
+    assert plan["total_padded"] == base
+    order = [(b["layer"], b["cls"]) for b in plan["buckets"]]
+    assert order == sorted(order) and len(set(order)) == len(order)
+
+
+# ------------------------------------------------------------------ closed-form memory model
+
+def test_memory_closed_form_golden():
+    """M_hzp of Section 4.1.1 at the paper's group sizes, values worked by hand."""
+    for N, z1, z2, z3, want in _rows("memory_model.txt"):
+        got = op.hzp_memory_bytes(int(N), int(z1), int(z2), int(z3))
+        assert got == Fraction(int(want)), (N, z1, z2, z3)
+
+
+@settings(max_examples=60, deadline=None)
+@given(descriptors(max_numel=2000))
+def test_per_rank_bytes_match_memory_model(d):
+    d = dict(d, tensor_class=None)                           # the paper's table: bf16 parameters
+    plan = op.make_plan(**d)
+    opt, grad, par = op.per_rank_bytes(plan)
+    Ptot = plan["total_padded"]
+    z1, z3 = plan["z1"], plan["z3"]
+    assert Fraction(opt + grad + par) == (Fraction(12 * Ptot, z1) + Fraction(4 * Ptot, z3)
+                                          + Fraction(2 * Ptot, z3))
+    assert opt == 12 * Ptot // z1 and grad == 4 * Ptot // z3 and par == 2 * Ptot // z3
+    if z1 == z3:                                             # collapses to 18N/Z (ZP) ...
+        assert opt + grad + par == 18 * Ptot // z1
+
+
+def test_vanilla_zero3_special_case():
+    plan = op.make_plan([2], [1000, 24], align=8, z3=16, z1=16)    # ... and to 18N/DP
+    assert sum(op.per_rank_bytes(plan)) * 16 == 18 * plan["total_padded"]
+
+
+# ------------------------------------------------------------------ special cases
+
+def test_group_size_one_is_whole_bucket():
+    plan = op.make_plan([3], [5, 17, 100], align=8, z3=1, z1=1)
+    b = plan["buckets"][0]
+    assert op.shard_range(plan, b, 1, 0) == (0, b["P"])
+    assert op.shard_range(plan, b, 3, 0) == (0, b["P"])
+    assert [plan["tensors"][t]["offset"] for t in range(3)] == [0, 8, 32]
+    assert b["payload_end"] == 132 and b["P"] == 136
+
+
+def test_exact_multiple_needs_no_padding():
+    plan = op.make_plan([1], [16 * 8 * 5], align=16, z3=2, z1=8)
+    b = plan["buckets"][0]
+    assert b["P"] == b["payload_end"] == 640 and b["S1"] == 80 and b["S3"] == 320
+
+
+def test_classes_split_buckets():
+    plan = op.make_plan([4, 1], [10, 20, 30, 40, 7], align=8, z3=2, z1=2,
+                        tensor_class=[0, 1, 0, 1, 1])
+    assert [(b["layer"], b["cls"], b["tensor_ids"]) for b in plan["buckets"]] == [
+        (0, 0, [0, 2]), (0, 1, [1, 3]), (1, 1, [4])]
+    assert op.find_bucket(plan, 1, 0) is None
+    assert [plan["tensors"][t]["offset"] for t in range(5)] == [0, 0, 16, 24, 0]
+    # P: bucket0 payload 46 -> 48; bucket1 payload 64 -> 64; bucket2 payload 7 -> 16
+    assert [b["P"] for b in plan["buckets"]] == [48, 64, 16]
+    assert [b["base"] for b in plan["buckets"]] == [0, 48, 112]
+    opt, grad, par = op.per_rank_bytes(plan)
+    assert (opt, grad, par) == (12 * 128 // 2, 4 * 128 // 2, (2 * 48 + 4 * 64 + 4 * 16) // 2)
+
+
+def test_rank_map_example():
+    # Z3 = 2, Z1 = 6, K = 3: ranks 0..5 -> (j, k, i)
+    plan = op.make_plan([1], [96], align=8, z3=2, z1=6)
+    got = [op.rank_to_indices(plan, r) for r in range(6)]
+    assert got == [(0, 0, 0), (1, 0, 3), (0, 1, 1), (1, 1, 4), (0, 2, 2), (1, 2, 5)]
+    b = plan["buckets"][0]
+    assert (b["P"], b["S3"], b["S1"]) == (96, 48, 16)
+    assert op.shard_range(plan, b, 1, 3) == (64, 16)
+    assert op.shard_range(plan, b, 3, 3) == (48, 48)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(align=12), dict(align=4), dict(z3=3, z1=8), dict(z3=0), dict(z2=4),
+    dict(tensor_numel=[0, 5]), dict(tensors_per_layer=[0, 2]), dict(tensor_class=[0, 2]),
+])
+def test_rejects_bad_descriptors(bad):
+    d = dict(tensors_per_layer=[2], tensor_numel=[3, 5], align=8, z3=2, z1=8)
+    d.update(bad)
+    with pytest.raises(op.PlanError):
+        op.make_plan(**d)
+
+
+# ------------------------------------------------------------------ hand-worked model shapes
+
+def _first_bucket_named(cfg, plan, layer_name):
+    return op.find_bucket(plan, cfg["layer_names"].index(layer_name), op.CLASS_BF16)
+
+
+def test_model_shaped_hand_values():
+    want = {r[0]: [int(x) for x in r[1:]] for r in _rows("layout_hand_values.txt")}
+    where = {"dense7b_layer": (1, "layer5"), "dense7b_head": (1, "head"),
+             "dense70b_layer": (2, "layer79"), "moe_layer": (3, "layer0"),
+             "tiny_embed": (0, "embed"), "tiny_layer": (0, "layer1")}
+    for key, (idx, lname) in where.items():
+        cfg = hzp_inputs.config(idx)
+        plan = op.make_plan(cfg["tensors_per_layer"], cfg["tensor_numel"], cfg["align"],
+                            cfg["z3"], cfg["z1"])
+        b = _first_bucket_named(cfg, plan, lname)
+        A, z3, z1, payload_end, P, S3, S1 = want[key]
+        assert (plan["align"], plan["z3"], plan["z1"]) == (A, z3, z1)
+        assert (b["payload_end"], b["P"], b["S3"], b["S1"]) == (payload_end, P, S3, S1), key
+
+
+def test_workload_shapes():
+    c0 = hzp_inputs.config(0)
+    assert len(c0["tensor_numel"]) == 16 and sum(c0["tensor_numel"]) == 1838336
+    c3 = hzp_inputs.config(3)
+    assert c3["tensors_per_layer"] == [199] * 24
+    c4 = hzp_inputs.config(4)
+    assert len(c4["tensor_numel"]) == 4096 and c4["tensors_per_layer"] == [64] * 64
+    assert min(c4["tensor_numel"]) >= 1 and max(c4["tensor_numel"]) <= 65536
+    plan = op.make_plan(c4["tensors_per_layer"], c4["tensor_numel"], c4["align"], c4["z3"],
+                        c4["z1"], tensor_class=c4["tensor_class"])
+    assert len(plan["buckets"]) == 128                       # a bf16 and an fp32 bucket per group
