@@ -1,0 +1,231 @@
+/*
+ * hzp.h -- C ABI of libhzp: the one-GPU share of the data-parallel hot path of
+ * Asynchronous Hierarchical ZeRO Parallelism (AsyncHZP) on AMD CDNA4 (gfx950).
+ *
+ * Each training step a rank (1) sums the gradient contributions that land on its
+ * shard, (2) applies Adam with decoupled weight decay to its ZeRO-1 shard of
+ * fp32 master weights / momentum / variance and casts the result to bf16, and
+ * (3) rebuilds bf16 parameter buffers out of the hierarchical ZeRO-1 / ZeRO-3
+ * layout.  The contributions of other ranks are buffers that already sit in this
+ * GPU's memory; no collective is issued here.
+ *
+ * Conventions for every entry point
+ *   - returns an hzp_status_t; never throws, aborts or synchronises the device;
+ *     hzp_last_error() gives a thread-local text for the last non-OK status;
+ *   - "device pointer": memory the current HIP device can address; "host array":
+ *     ordinary host memory read during the call and not retained;
+ *   - all device buffers are owned by the caller.  The library allocates device
+ *     memory only for small per-plan lookup tables, created on the first call
+ *     that needs them (that one call may synchronise) and freed by hzp_plan_free;
+ *   - kernel work is enqueued on the given stream and the call returns at once;
+ *     a plan is immutable and may be used from several host threads and streams
+ *     at the same time (the paper issues these operations from extra threads on
+ *     dedicated streams, Section 4.2);
+ *   - bf16 buffers hold 16-bit patterns (upper half of an IEEE binary32).
+ */
+#ifndef HZP_H
+#define HZP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Same declaration as the HIP runtime's; repeated so that this header needs no HIP include. */
+typedef struct ihipStream_t *hipStream_t;
+
+typedef struct hzp_plan hzp_plan_t;     /* opaque, host-side, immutable */
+
+typedef enum {
+    HZP_OK = 0,
+    HZP_ERR_INVALID_ARG = 1,    /* NULL where a pointer is required, inconsistent counts, step 0 ... */
+    HZP_ERR_RANGE = 2,          /* layer / rank / tensor id / level outside the plan */
+    HZP_ERR_UNSUPPORTED = 3,    /* a valid request this build does not cover (e.g. Z3 does not divide Z1) */
+    HZP_ERR_ALIGN = 4,          /* a device pointer is not aligned as the entry point requires */
+    HZP_ERR_NOMEM = 5,
+    HZP_ERR_HIP = 6             /* a HIP runtime call or a kernel launch failed */
+} hzp_status_t;
+
+/* Parameter / gradient element type of a bucket.  BF16: bf16 gradient contributions and bf16
+ * parameters out (Table 1 of the paper).  F32: fp32 contributions and an fp32 parameter copy
+ * out (1-D norm / bias states that are kept in full precision). */
+typedef enum { HZP_CLASS_BF16 = 0, HZP_CLASS_F32 = 1 } hzp_class_t;
+
+#define HZP_MAX_REPLICAS 32u    /* largest R accepted by the reduce / update entry points */
+#define HZP_MAX_GROUP    64u    /* largest number of shards one gather call concatenates */
+
+/* ------------------------------------------------------------------------------------------
+ * Layout planner.
+ *
+ * Section 4.1.1 of the paper gives three independent sharding-group sizes; its memory model
+ * M_hzp = 12N/Z1 + 4N/Z2 + 2N/Z3 fixes which is which: Z1 shards the optimizer states
+ * (12 B/parameter), Z2 the gradients (4 B), Z3 the parameters (2 B).  Parameters and gradients
+ * are sharded in a small group, optimizer states in a larger one (Figure 1, Section 3.1).
+ *
+ * The paper does not say how tensors are laid out inside a shardable buffer; this library uses
+ * one flat bucket per (layer, class):
+ *     off_0 = 0,  off_{t+1} = round_up(off_t + n_t, A)        every tensor starts A-aligned
+ *     payload_end = off_last + n_last
+ *     P  = round_up(payload_end, A*Z1)                         padded length (padding holds 0)
+ *     S3 = P/Z3   ZeRO-3 shard j covers [j*S3, (j+1)*S3)       parameters, gradients
+ *     S1 = P/Z1   ZeRO-1 shard i covers [i*S1, (i+1)*S1)       master, momentum, variance
+ *     rank r in [0,Z1):  j = r mod Z3,  k = r div Z3,  i = j*K + k,  K = Z1/Z3
+ * so ZeRO-1 shard i lies inside ZeRO-3 shard j, and the K owners of one ZeRO-3 shard are the
+ * ranks j, j+Z3, j+2*Z3, ...  Buckets are ordered by (layer, class); `base` is the running sum
+ * of P in that order.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    uint32_t n_layers;                  /* >= 1 */
+    const uint32_t *tensors_per_layer;  /* host array [n_layers], each >= 1 */
+    const uint64_t *tensor_numel;       /* host array [sum of tensors_per_layer], each >= 1 */
+    const uint8_t *tensor_class;        /* host array of hzp_class_t per tensor; NULL: all BF16 */
+    const float *tensor_wd_mult;        /* host array, multiplies weight_decay per tensor; NULL: all 1 */
+    uint32_t align_elems;               /* A: power of two, >= 8 */
+    uint32_t z3, z2, z1;                /* z2 is 0 or equal to z3; z3 must divide z1 */
+} hzp_plan_desc_t;
+
+typedef struct {
+    uint32_t n_layers, n_buckets, n_tensors;
+    uint32_t align_elems, z3, z2, z1, k;    /* k = z1 / z3 */
+    uint64_t total_padded;                   /* sum of P over all buckets */
+} hzp_plan_info_t;
+
+typedef struct {
+    uint32_t layer;
+    uint32_t cls;
+    uint32_t n_tensors;
+    uint32_t bucket_index;      /* position in (layer, class) order */
+    uint64_t payload_end;       /* end of the last tensor */
+    uint64_t padded;            /* P */
+    uint64_t s3;                /* P / Z3 */
+    uint64_t s1;                /* P / Z1 */
+    uint64_t base;              /* start of the bucket in the global flat address space */
+} hzp_bucket_info_t;
+
+typedef struct {
+    uint32_t layer;
+    uint32_t cls;
+    uint32_t bucket_index;
+    uint32_t index_in_bucket;   /* position among the bucket's tensors (order of tensor_out[]) */
+    uint64_t offset;            /* bucket-relative start, a multiple of A */
+    uint64_t numel;
+    float wd_mult;
+} hzp_tensor_info_t;
+
+/* Build a plan.  Pure 64-bit integer work on the host: makes no HIP call and needs no GPU.
+ * Copies everything it needs from `desc`.  *out is owned by the library until hzp_plan_free.
+ * Errors: INVALID_ARG (NULL, zero counts, bad alignment, unknown class), UNSUPPORTED
+ * (z3 does not divide z1, z2 not in {0, z3}), NOMEM. */
+hzp_status_t hzp_plan(const hzp_plan_desc_t *desc, hzp_plan_t **out);
+
+/* Free a plan and its device tables.  NULL is allowed.  The caller must make sure that no kernel
+ * launched with this plan is still running. */
+void hzp_plan_free(hzp_plan_t *plan);
+
+/* Read-back of the layout (what the tests compare with the oracle, bit for bit). */
+hzp_status_t hzp_plan_info(const hzp_plan_t *plan, hzp_plan_info_t *out);
+/* RANGE if the layer has no bucket of that class. */
+hzp_status_t hzp_plan_bucket(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, hzp_bucket_info_t *out);
+hzp_status_t hzp_plan_tensor(const hzp_plan_t *plan, uint32_t tensor_id, hzp_tensor_info_t *out);
+/* rank -> ZeRO-3 index j, outer index k, ZeRO-1 shard index i. */
+hzp_status_t hzp_plan_rank(const hzp_plan_t *plan, uint32_t rank, uint32_t *j, uint32_t *k, uint32_t *i);
+/* Bucket-relative [begin, begin+len) of the rank's shard; level 3: parameter / gradient shard,
+ * level 1: optimizer-state shard. */
+hzp_status_t hzp_plan_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level, uint32_t rank,
+                            uint64_t *begin, uint64_t *len);
+/* Bytes one rank holds: 12*S1 of optimizer state, 4*P/Z2 of fp32 gradient and the parameter
+ * shard (2 or 4 bytes per element), summed over buckets -- M_hzp of Section 4.1.1 with N -> P. */
+hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt_bytes, uint64_t *grad_bytes,
+                            uint64_t *param_bytes);
+
+/* ------------------------------------------------------------------------------------------
+ * Gradient reduction on the rank's shard: the arithmetic half of the per-layer reduce-scatter
+ * ("performed using the float32 data type", Section 4.1.2, Backward Pass) together with the
+ * final reduction across replicas of the model states (Section 4.1.2, Optimizer Step).
+ *
+ *     s      = ((G_0[x] + G_1[x]) + G_2[x]) + ...      fp32, strictly in the order r = 0..R-1
+ *     out[x] = accumulate ? out[x] + scale*s : scale*s  one multiply, one add, no fused rounding
+ *
+ * for x in [0, n), n = S1 (level 1) or S3 (level 3) of bucket (layer, cls).  The result equals
+ * the scalar definition bit for bit.
+ *   grad_slices : host array [R] of device pointers; entry r points at element 0 of the rank's
+ *                 slice inside contribution r (bf16 for class BF16, fp32 for class F32), n
+ *                 elements, 16-byte aligned
+ *   R           : 1 .. HZP_MAX_REPLICAS
+ *   out_f32     : device pointer, n floats, 16-byte aligned; read first when accumulate != 0;
+ *                 must not overlap any input
+ * Errors: INVALID_ARG, RANGE (layer / class / level / rank), UNSUPPORTED (R too large), ALIGN, HIP.
+ * ------------------------------------------------------------------------------------------ */
+hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level, uint32_t rank,
+                              const void *const *grad_slices, uint32_t R, float scale, int accumulate,
+                              float *out_f32, hipStream_t stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Fused shard update: reduction as above (scale = grad_scale, no accumulate), then Adam with
+ * decoupled weight decay on the rank's ZeRO-1 shard (mixed-precision Adam on the local
+ * optimizer shard, Section 4.1.1 and Section 4.1.2 "Optimizer Step"), then the cast that
+ * produces the rank's piece of the new bf16 parameters:
+ *
+ *     g  = grad_scale * sum_r G_r[x]
+ *     m  = beta1*m + (1-beta1)*g
+ *     v  = beta2*v + (1-beta2)*g*g
+ *     u  = (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps)
+ *     p  = p - lr*(u + weight_decay*wd_mult(tensor of x)*p)         p on the right is the old p
+ *     param_out[x] = bf16_round_to_nearest_even(p)   (class F32: param_out[x] = p)
+ *
+ * computed in fp32 (results agree with a double-precision evaluation to about 1e-6 relative;
+ * they are not promised bit for bit).  Padding positions must hold 0 in every input and then
+ * stay 0.  One call covers the buckets of class `cls` of layers [layer_begin, layer_end); a layer
+ * without such a bucket is skipped and its array entries are ignored.  Per-layer arrays are
+ * host arrays indexed by (layer - layer_begin):
+ *   grad_slices : [(layer_end-layer_begin) * max(R,1)], entry (l*R + r) as in hzp_reduce_shard
+ *                 at level 1.  R == 0: a single fp32 slice per layer that is already reduced
+ *                 (grad_scale is still applied)
+ *   master,m,v  : device pointers to S1 floats each, 16-byte aligned, updated in place
+ *   param_out   : device pointers to S1 bf16 (class BF16) or S1 floats (class F32), 16-byte
+ *                 aligned; the array itself may be NULL (no cast output)
+ * No buffer may overlap another.  step is 1-based.
+ * Errors: INVALID_ARG (NULL, step 0, empty range), RANGE, UNSUPPORTED (R too large), ALIGN, HIP.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay, grad_scale;
+    uint32_t step;
+} hzp_adamw_t;
+
+hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, uint32_t cls,
+                             uint32_t rank, const hzp_adamw_t *hyper, const void *const *grad_slices,
+                             uint32_t R, float *const *master, float *const *m, float *const *v,
+                             void *const *param_out, hipStream_t stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Gather: the data-movement half of the two all-gathers of Section 4.1.2.
+ *   level 1 : the post-step all-gather that rebuilds a ZeRO-3 parameter shard from the K
+ *             ZeRO-1 owners' outputs:   bucket_out[k*S1 + x] = shard_ptrs[k][x],  n_shards == K
+ *   level 3 : the all-gather that rebuilds a layer's parameters from the Z3 ZeRO-3 shards before
+ *             the layer is used:        bucket_out[j*S3 + x] = shard_ptrs[j][x],  n_shards == Z3
+ *             and / or, per tensor t of the bucket (padding dropped):
+ *                                       tensor_out[t][y] = bucket[offset_t + y],  y < numel_t
+ * Bit copies; elements are bf16 (class BF16) or fp32 (class F32).
+ *   shard_ptrs : host array [n_shards] of device pointers, 16-byte aligned
+ *   bucket_out : device pointer to S3 (level 1) or P (level 3) elements, 16-byte aligned; may be
+ *                NULL at level 3 when tensor_out is given
+ *   tensor_out : level 3 only, may be NULL; host array [n_tensors of the bucket] of device
+ *                pointers, each to numel_t elements, element-aligned only
+ * At least one output is required; outputs must not overlap inputs.
+ * Errors: INVALID_ARG (n_shards mismatch, no output, tensor_out at level 1), RANGE, UNSUPPORTED
+ * (more than HZP_MAX_GROUP shards), ALIGN, NOMEM, HIP.
+ * ------------------------------------------------------------------------------------------ */
+hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level,
+                              const void *const *shard_ptrs, uint32_t n_shards, void *bucket_out,
+                              void *const *tensor_out, hipStream_t stream);
+
+/* Text of the calling thread's last non-OK status ("" if none).  Valid until that thread's next
+ * failing call. */
+const char *hzp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HZP_H */

@@ -1,0 +1,233 @@
+"""ctypes binding of libhzp: argument marshalling only, every step runs in the library.
+
+Function names and argument order follow ``include/hzp.h``.  Device buffers may be given as
+torch tensors (their ``data_ptr()`` is taken) or as integer addresses; a stream may be a
+``torch.cuda.Stream``, an integer ``hipStream_t`` or None (torch's current stream).
+There is no fallback: if ``libhzp.so`` has not been built, importing this module fails.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhzp.so")
+
+HZP_OK, HZP_ERR_INVALID_ARG, HZP_ERR_RANGE, HZP_ERR_UNSUPPORTED, HZP_ERR_ALIGN, HZP_ERR_NOMEM, \
+    HZP_ERR_HIP = range(7)
+HZP_CLASS_BF16, HZP_CLASS_F32 = 0, 1
+HZP_MAX_REPLICAS, HZP_MAX_GROUP = 32, 64
+_STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSUPPORTED",
+                 "HZP_ERR_ALIGN", "HZP_ERR_NOMEM", "HZP_ERR_HIP"]
+
+EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
+           "hzp_plan_rank", "hzp_plan_shard", "hzp_plan_bytes", "hzp_reduce_shard",
+           "hzp_adamw_shard", "hzp_gather_layer", "hzp_last_error"]
+
+
+class HzpError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("%s: %s" % (_STATUS_NAMES[status] if 0 <= status < 7 else status, text))
+        self.status = status
+
+
+class PlanDesc(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_uint32),
+                ("tensors_per_layer", ctypes.POINTER(ctypes.c_uint32)),
+                ("tensor_numel", ctypes.POINTER(ctypes.c_uint64)),
+                ("tensor_class", ctypes.POINTER(ctypes.c_uint8)),
+                ("tensor_wd_mult", ctypes.POINTER(ctypes.c_float)),
+                ("align_elems", ctypes.c_uint32),
+                ("z3", ctypes.c_uint32), ("z2", ctypes.c_uint32), ("z1", ctypes.c_uint32)]
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_uint32), ("n_buckets", ctypes.c_uint32),
+                ("n_tensors", ctypes.c_uint32), ("align_elems", ctypes.c_uint32),
+                ("z3", ctypes.c_uint32), ("z2", ctypes.c_uint32), ("z1", ctypes.c_uint32),
+                ("k", ctypes.c_uint32), ("total_padded", ctypes.c_uint64)]
+
+
+class BucketInfo(ctypes.Structure):
+    _fields_ = [("layer", ctypes.c_uint32), ("cls", ctypes.c_uint32),
+                ("n_tensors", ctypes.c_uint32), ("bucket_index", ctypes.c_uint32),
+                ("payload_end", ctypes.c_uint64), ("padded", ctypes.c_uint64),
+                ("s3", ctypes.c_uint64), ("s1", ctypes.c_uint64), ("base", ctypes.c_uint64)]
+
+
+class TensorInfo(ctypes.Structure):
+    _fields_ = [("layer", ctypes.c_uint32), ("cls", ctypes.c_uint32),
+                ("bucket_index", ctypes.c_uint32), ("index_in_bucket", ctypes.c_uint32),
+                ("offset", ctypes.c_uint64), ("numel", ctypes.c_uint64),
+                ("wd_mult", ctypes.c_float)]
+
+
+class AdamW(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("grad_scale", ctypes.c_float), ("step", ctypes.c_uint32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libhzp.so is not built: run `python paper_2510_20111_amd/build.py` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, u32, u64p = ctypes.c_void_p, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint64)
+    u32p = ctypes.POINTER(ctypes.c_uint32)
+    L.hzp_plan.restype = ctypes.c_int
+    L.hzp_plan.argtypes = [ctypes.POINTER(PlanDesc), ctypes.POINTER(vp)]
+    L.hzp_plan_free.restype = None
+    L.hzp_plan_free.argtypes = [vp]
+    L.hzp_plan_info.restype = ctypes.c_int
+    L.hzp_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+    L.hzp_plan_bucket.restype = ctypes.c_int
+    L.hzp_plan_bucket.argtypes = [vp, u32, u32, ctypes.POINTER(BucketInfo)]
+    L.hzp_plan_tensor.restype = ctypes.c_int
+    L.hzp_plan_tensor.argtypes = [vp, u32, ctypes.POINTER(TensorInfo)]
+    L.hzp_plan_rank.restype = ctypes.c_int
+    L.hzp_plan_rank.argtypes = [vp, u32, u32p, u32p, u32p]
+    L.hzp_plan_shard.restype = ctypes.c_int
+    L.hzp_plan_shard.argtypes = [vp, u32, u32, ctypes.c_int, u32, u64p, u64p]
+    L.hzp_plan_bytes.restype = ctypes.c_int
+    L.hzp_plan_bytes.argtypes = [vp, u64p, u64p, u64p]
+    L.hzp_reduce_shard.restype = ctypes.c_int
+    L.hzp_reduce_shard.argtypes = [vp, u32, u32, ctypes.c_int, u32, vp, u32, ctypes.c_float,
+                                   ctypes.c_int, vp, vp]
+    L.hzp_adamw_shard.restype = ctypes.c_int
+    L.hzp_adamw_shard.argtypes = [vp, u32, u32, u32, u32, ctypes.POINTER(AdamW), vp, u32,
+                                  vp, vp, vp, vp, vp]
+    L.hzp_gather_layer.restype = ctypes.c_int
+    L.hzp_gather_layer.argtypes = [vp, u32, u32, ctypes.c_int, vp, u32, vp, vp, vp]
+    L.hzp_last_error.restype = ctypes.c_char_p
+    L.hzp_last_error.argtypes = []
+    return L
+
+
+_L = _load()
+
+
+def _check(status):
+    if status != HZP_OK:
+        raise HzpError(status, hzp_last_error())
+
+
+def hzp_last_error():
+    return _L.hzp_last_error().decode("utf-8", "replace")
+
+
+def _addr(x):
+    """Device address of a torch tensor, or the integer itself."""
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def ptr_array(items):
+    """Host array of device pointers (void*[]) from tensors / integer addresses."""
+    if isinstance(items, ctypes.Array):
+        return items
+    return (ctypes.c_void_p * len(items))(*[_addr(x) for x in items])
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Plan:
+    """Owner of an ``hzp_plan_t*``; freed when the object dies."""
+
+    def __init__(self, handle, keep):
+        self.handle = handle
+        self._keep = keep
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            _L.hzp_plan_free(self.handle)
+            self.handle = None
+
+    def info(self):
+        out = PlanInfo()
+        _check(_L.hzp_plan_info(self.handle, ctypes.byref(out)))
+        return out
+
+    def bucket(self, layer, cls=HZP_CLASS_BF16):
+        out = BucketInfo()
+        _check(_L.hzp_plan_bucket(self.handle, layer, cls, ctypes.byref(out)))
+        return out
+
+    def has_bucket(self, layer, cls):
+        out = BucketInfo()
+        return _L.hzp_plan_bucket(self.handle, layer, cls, ctypes.byref(out)) == HZP_OK
+
+    def tensor(self, tensor_id):
+        out = TensorInfo()
+        _check(_L.hzp_plan_tensor(self.handle, tensor_id, ctypes.byref(out)))
+        return out
+
+    def rank(self, rank):
+        j, k, i = ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_uint32()
+        _check(_L.hzp_plan_rank(self.handle, rank, ctypes.byref(j), ctypes.byref(k), ctypes.byref(i)))
+        return j.value, k.value, i.value
+
+    def shard(self, layer, cls, level, rank):
+        b, n = ctypes.c_uint64(), ctypes.c_uint64()
+        _check(_L.hzp_plan_shard(self.handle, layer, cls, level, rank, ctypes.byref(b), ctypes.byref(n)))
+        return b.value, n.value
+
+    def bytes(self):
+        o, g, p = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
+        _check(_L.hzp_plan_bytes(self.handle, ctypes.byref(o), ctypes.byref(g), ctypes.byref(p)))
+        return o.value, g.value, p.value
+
+
+def hzp_plan(tensors_per_layer, tensor_numel, align, z3, z1, z2=0, tensor_class=None,
+             tensor_wd_mult=None):
+    n_layers, n = len(tensors_per_layer), len(tensor_numel)
+    tpl = (ctypes.c_uint32 * n_layers)(*tensors_per_layer)
+    numel = (ctypes.c_uint64 * n)(*tensor_numel)
+    cls = (ctypes.c_uint8 * n)(*tensor_class) if tensor_class is not None else None
+    wd = (ctypes.c_float * n)(*tensor_wd_mult) if tensor_wd_mult is not None else None
+    desc = PlanDesc(n_layers, tpl, numel, cls, wd, align, z3, z2, z1)
+    handle = ctypes.c_void_p()
+    _check(_L.hzp_plan(ctypes.byref(desc), ctypes.byref(handle)))
+    return Plan(handle, None)
+
+
+def hzp_plan_free(plan):
+    plan.__del__()
+
+
+def hzp_reduce_shard(plan, layer, cls, level, rank, grad_slices, scale, accumulate, out_f32,
+                     stream=None, R=None):
+    arr = ptr_array(grad_slices)
+    _check(_L.hzp_reduce_shard(plan.handle, layer, cls, level, rank, arr,
+                               len(arr) if R is None else R, scale, int(bool(accumulate)),
+                               _addr(out_f32), _stream(stream)))
+
+
+def adamw_hyper(lr, beta1, beta2, eps, weight_decay, grad_scale, step):
+    return AdamW(lr, beta1, beta2, eps, weight_decay, grad_scale, step)
+
+
+def hzp_adamw_shard(plan, layer_begin, layer_end, cls, rank, hyper, grad_slices, R, master, m, v,
+                    param_out, stream=None):
+    """grad_slices: flat sequence, entry (layer-layer_begin)*max(R,1) + r."""
+    _check(_L.hzp_adamw_shard(plan.handle, layer_begin, layer_end, cls, rank, ctypes.byref(hyper),
+                              ptr_array(grad_slices), R, ptr_array(master), ptr_array(m),
+                              ptr_array(v), ptr_array(param_out) if param_out is not None else None,
+                              _stream(stream)))
+
+
+def hzp_gather_layer(plan, layer, cls, level, shard_ptrs, bucket_out=None, tensor_out=None,
+                     stream=None, n_shards=None):
+    arr = ptr_array(shard_ptrs)
+    _check(_L.hzp_gather_layer(plan.handle, layer, cls, level, arr,
+                               len(arr) if n_shards is None else n_shards, _addr(bucket_out),
+                               ptr_array(tensor_out) if tensor_out is not None else None,
+                               _stream(stream)))

@@ -1,0 +1,143 @@
+// Argument checking of the kernel-launching entry points of libhzp.  Everything that could make
+// a kernel read or write outside a caller's buffer is rejected here with a status code: the
+// kernels themselves trust their arguments.
+#include <hip/hip_runtime_api.h>
+
+#include <vector>
+
+#include "hzp_internal.hpp"
+
+namespace hzp {
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace hzp
+
+using namespace hzp;
+
+extern "C" hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level,
+                                         uint32_t rank, const void *const *grad_slices, uint32_t R,
+                                         float scale, int accumulate, float *out_f32, hipStream_t stream)
+{
+    if (!plan || !grad_slices || !out_f32)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: NULL plan, slice array or output");
+    const BucketRec *b = find_bucket(plan, layer, cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_reduce_shard: no bucket (layer %u, class %u)", layer, cls);
+    if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_reduce_shard: rank %u of %u", rank, plan->z1);
+    if (level != 1 && level != 3)
+        return fail(HZP_ERR_RANGE, "hzp_reduce_shard: level %d is neither 1 nor 3", level);
+    if (R == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: R must be at least 1");
+    if (R > HZP_MAX_REPLICAS)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_reduce_shard: R=%u exceeds %u", R, HZP_MAX_REPLICAS);
+    const uint64_t n = level == 1 ? b->S1 : b->S3;
+    if (n / 8 > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_reduce_shard: shard too large");
+    for (uint32_t r = 0; r < R; ++r) {
+        if (!grad_slices[r]) return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: slice %u is NULL", r);
+        if (!aligned16(grad_slices[r]))
+            return fail(HZP_ERR_ALIGN, "hzp_reduce_shard: slice %u is not 16-byte aligned", r);
+    }
+    if (!aligned16(out_f32)) return fail(HZP_ERR_ALIGN, "hzp_reduce_shard: output is not 16-byte aligned");
+    return launch_reduce(cls == HZP_CLASS_F32, grad_slices, R, n, scale, accumulate, out_f32, stream);
+}
+
+extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                                        uint32_t cls, uint32_t rank, const hzp_adamw_t *hy,
+                                        const void *const *grad_slices, uint32_t R, float *const *master,
+                                        float *const *m, float *const *v, void *const *param_out,
+                                        hipStream_t stream)
+{
+    if (!plan || !hy || !grad_slices || !master || !m || !v)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: NULL plan, hyper-parameters or pointer array");
+    if (layer_begin >= layer_end)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: empty layer range [%u, %u)", layer_begin, layer_end);
+    if (layer_end > plan->n_layers)
+        return fail(HZP_ERR_RANGE, "hzp_adamw_shard: layer_end %u of %u", layer_end, plan->n_layers);
+    if (cls > 1) return fail(HZP_ERR_RANGE, "hzp_adamw_shard: class %u", cls);
+    if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_adamw_shard: rank %u of %u", rank, plan->z1);
+    if (hy->step == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: step is 1-based");
+    if (R > HZP_MAX_REPLICAS)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: R=%u exceeds %u", R, HZP_MAX_REPLICAS);
+    const bool prereduced = (R == 0);
+    const uint32_t per_layer = prereduced ? 1u : R;
+    const bool g32 = prereduced || cls == HZP_CLASS_F32;
+    const bool o32 = cls == HZP_CLASS_F32;
+    const uint64_t j = rank % plan->z3, k = rank / plan->z3;
+
+    std::vector<FusedSegment> segs;
+    try {
+        segs.reserve(layer_end - layer_begin);
+    } catch (const std::bad_alloc &) {
+        return fail(HZP_ERR_NOMEM, "hzp_adamw_shard: out of host memory");
+    }
+    for (uint32_t layer = layer_begin; layer < layer_end; ++layer) {
+        const BucketRec *b = find_bucket(plan, layer, cls);
+        if (!b) continue;                       // this layer has no tensor of the class
+        const size_t idx = layer - layer_begin;
+        FusedSegment f{};
+        f.grads = grad_slices + idx * per_layer;
+        f.master = master[idx];
+        f.m = m[idx];
+        f.v = v[idx];
+        f.out = param_out ? param_out[idx] : nullptr;
+        f.n = b->S1;
+        f.first_slot = b->first_slot;
+        f.n_tensors = b->n_tensors;
+        f.shard_begin = (j * plan->K + k) * b->S1;
+        if (f.n / 8 > 0x7FFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: shard too large");
+        if (!f.master || !f.m || !f.v)
+            return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: layer %u: NULL state pointer", layer);
+        if (!aligned16(f.master) || !aligned16(f.m) || !aligned16(f.v) || !aligned16(f.out))
+            return fail(HZP_ERR_ALIGN, "hzp_adamw_shard: layer %u: state or output not 16-byte aligned", layer);
+        if (param_out && !f.out)
+            return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: layer %u: NULL output pointer", layer);
+        for (uint32_t r = 0; r < per_layer; ++r) {
+            if (!f.grads[r])
+                return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: layer %u: slice %u is NULL", layer, r);
+            if (!aligned16(f.grads[r]))
+                return fail(HZP_ERR_ALIGN, "hzp_adamw_shard: layer %u: slice %u not 16-byte aligned", layer, r);
+        }
+        segs.push_back(f);
+    }
+    if (segs.empty()) return HZP_OK;
+    return launch_fused(plan, g32, o32, per_layer, segs.data(), segs.size(), *hy, stream);
+}
+
+extern "C" hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level,
+                                         const void *const *shard_ptrs, uint32_t n_shards, void *bucket_out,
+                                         void *const *tensor_out, hipStream_t stream)
+{
+    if (!plan || !shard_ptrs) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer: NULL plan or shard array");
+    const BucketRec *b = find_bucket(plan, layer, cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_gather_layer: no bucket (layer %u, class %u)", layer, cls);
+    if (level != 1 && level != 3)
+        return fail(HZP_ERR_RANGE, "hzp_gather_layer: level %d is neither 1 nor 3", level);
+    const uint32_t want = level == 1 ? plan->K : plan->z3;
+    if (n_shards != want)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer: level %d takes %u shards, got %u", level, want,
+                    n_shards);
+    if (n_shards > HZP_MAX_GROUP)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layer: %u shards exceed %u", n_shards, HZP_MAX_GROUP);
+    if (level == 1 && tensor_out)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer: tensor_out is a level-3 output");
+    if (!bucket_out && !tensor_out) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer: no output given");
+    const uint32_t es = cls == HZP_CLASS_F32 ? 4u : 2u;
+    for (uint32_t s = 0; s < n_shards; ++s) {
+        if (!shard_ptrs[s]) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer: shard %u is NULL", s);
+        if (!aligned16(shard_ptrs[s]))
+            return fail(HZP_ERR_ALIGN, "hzp_gather_layer: shard %u is not 16-byte aligned", s);
+    }
+    if (!aligned16(bucket_out)) return fail(HZP_ERR_ALIGN, "hzp_gather_layer: bucket_out is not 16-byte aligned");
+    if (tensor_out)
+        for (uint32_t t = 0; t < b->n_tensors; ++t) {
+            if (!tensor_out[t]) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer: tensor_out[%u] is NULL", t);
+            if (reinterpret_cast<uintptr_t>(tensor_out[t]) % es)
+                return fail(HZP_ERR_ALIGN, "hzp_gather_layer: tensor_out[%u] is not element-aligned", t);
+        }
+    const uint64_t len = level == 1 ? b->S1 : b->S3;
+    if (bucket_out) {
+        hzp_status_t st = launch_concat(shard_ptrs, n_shards, len * es, bucket_out, stream);
+        if (st != HZP_OK) return st;
+    }
+    if (tensor_out) return launch_unpack(plan, *b, shard_ptrs, n_shards, tensor_out, stream);
+    return HZP_OK;
+}

@@ -1,0 +1,99 @@
+// Internal declarations shared by the host sources of libhzp (not part of the ABI).
+#pragma once
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "hzp.h"
+
+namespace hzp {
+
+// Set the calling thread's error text and hand the status back.
+hzp_status_t fail(hzp_status_t st, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
+struct TensorRec {
+    uint32_t layer;
+    uint32_t cls;
+    uint32_t bucket;
+    uint32_t index_in_bucket;
+    uint64_t offset;
+    uint64_t numel;
+    float wd_mult;
+};
+
+// A maximal run of one tensor that lies inside one ZeRO-3 shard.  The unpack kernel walks
+// pieces in fixed-size chunks; `chunk_begin` is the running chunk count before this piece.
+struct Piece {
+    uint64_t src_off;       // element offset inside shard `shard`
+    uint64_t dst_off;       // element offset inside the tensor
+    uint64_t len;           // elements
+    uint32_t shard;         // ZeRO-3 index j
+    uint32_t tensor;        // index in bucket
+    uint32_t chunk_begin;
+    uint32_t pad_;
+};
+
+struct BucketRec {
+    uint32_t layer;
+    uint32_t cls;
+    uint32_t first_slot;    // first entry of this bucket in the per-bucket-ordered tables
+    uint32_t n_tensors;
+    uint64_t payload_end, P, S3, S1, base;
+    std::vector<uint32_t> tensor_ids;
+    std::vector<Piece> pieces;
+    uint32_t n_chunks;
+    uint32_t piece_slot;    // first entry of this bucket in the device piece table
+};
+
+// Lookup tables of one plan on one device.
+struct DeviceTables {
+    int device = -1;
+    uint64_t *tensor_off = nullptr;     // [n_tensors] bucket-relative offsets, bucket after bucket
+    float *tensor_wd = nullptr;         // [n_tensors] weight-decay multipliers, same order
+    Piece *pieces = nullptr;            // all buckets' pieces, bucket after bucket
+};
+
+constexpr uint32_t kUnpackChunk = 4096;   // elements one wavefront moves per chunk
+
+}  // namespace hzp
+
+struct hzp_plan {
+    uint32_t n_layers, align, z3, z2, z1, K;
+    uint64_t total_padded;
+    bool uniform_wd;                            // every multiplier is 1: no table lookups
+    std::vector<hzp::TensorRec> tensors;        // by tensor id
+    std::vector<hzp::BucketRec> buckets;        // by (layer, class)
+    std::vector<int32_t> bucket_of;             // [layer*2 + cls] -> bucket index or -1
+    std::vector<uint64_t> slot_off;             // per-bucket-ordered copies for the device
+    std::vector<float> slot_wd;
+    mutable std::mutex mu;
+    mutable std::vector<hzp::DeviceTables> dev; // one entry per device that has used the plan
+};
+
+namespace hzp {
+const BucketRec *find_bucket(const hzp_plan_t *plan, uint32_t layer, uint32_t cls);
+
+// One shard segment (one layer bucket) of a fused update call.
+struct FusedSegment {
+    const void *const *grads;   // R device pointers (host array)
+    float *master, *m, *v;
+    void *out;                  // nullable
+    uint64_t n;                 // elements, a multiple of 8
+    uint32_t first_slot, n_tensors;     // the bucket's rows in the weight-decay tables
+    uint64_t shard_begin;       // bucket position of element 0
+};
+
+// Launchers; their arguments have been validated by the entry points.
+hzp_status_t launch_reduce(bool g32, const void *const *slices, uint32_t R, uint64_t n, float scale,
+                           int accumulate, float *out, hipStream_t stream);
+hzp_status_t launch_fused(const hzp_plan_t *plan, bool g32, bool o32, uint32_t R, const FusedSegment *segs,
+                          size_t nseg, const hzp_adamw_t &hy, hipStream_t stream);
+hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t bytes_per_shard, void *dst,
+                           hipStream_t stream);
+hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const void *const *shards,
+                           uint32_t n_shards, void *const *tensors, hipStream_t stream);
+// Tables for the current device (creates them on first use).  Defined with the launchers.
+hzp_status_t device_tables(const hzp_plan_t *plan, const DeviceTables **out);
+void free_device_tables(hzp_plan_t *plan);
+}  // namespace hzp

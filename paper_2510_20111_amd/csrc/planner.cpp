@@ -1,0 +1,286 @@
+// Layout planner of libhzp: layers -> padded flat buckets -> ZeRO-3 / ZeRO-1 shard ranges.
+// Host-only 64-bit integer code; it makes no HIP call, so a plan can be built without a GPU.
+//
+// Group sizes follow the memory model of Section 4.1.1 (M_hzp = 12N/Z1 + 4N/Z2 + 2N/Z3):
+// Z1 shards the optimizer states, Z2 the gradients, Z3 the parameters.  The bucket rule
+// (A-aligned tensor starts, zero padding up to a multiple of A*Z1) and the rank map
+// (j = r mod Z3, k = r div Z3, i = j*K + k) are this library's own choices; the paper only
+// asks that parameters and gradients live in a small group and optimizer states in a larger
+// one (Figure 1, Section 3.1).
+#include <cstdarg>
+#include <cstdio>
+#include <new>
+
+#include "hzp_internal.hpp"
+
+namespace hzp {
+
+static thread_local char g_err[512] = "";
+
+hzp_status_t fail(hzp_status_t st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+const BucketRec *find_bucket(const hzp_plan_t *plan, uint32_t layer, uint32_t cls)
+{
+    if (layer >= plan->n_layers || cls > 1) return nullptr;
+    int32_t b = plan->bucket_of[layer * 2 + cls];
+    return b < 0 ? nullptr : &plan->buckets[b];
+}
+
+static bool round_up(uint64_t x, uint64_t q, uint64_t *out)
+{
+    uint64_t t;
+    if (__builtin_add_overflow(x, q - 1, &t)) return false;
+    *out = t / q * q;
+    return true;
+}
+
+// Split every tensor of the bucket at ZeRO-3 shard boundaries and number the chunks.
+static bool build_pieces(const hzp_plan_t *plan, BucketRec &b)
+{
+    uint64_t chunks = 0;
+    for (uint32_t s = 0; s < b.n_tensors; ++s) {
+        const TensorRec &t = plan->tensors[b.tensor_ids[s]];
+        uint64_t pos = t.offset, end = t.offset + t.numel;
+        while (pos < end) {
+            uint64_t j = pos / b.S3;
+            uint64_t stop = (j + 1) * b.S3 < end ? (j + 1) * b.S3 : end;
+            Piece p{};
+            p.src_off = pos - j * b.S3;
+            p.dst_off = pos - t.offset;
+            p.len = stop - pos;
+            p.shard = (uint32_t)j;
+            p.tensor = s;
+            if (chunks > 0xFFFFFFFFull) return false;
+            p.chunk_begin = (uint32_t)chunks;
+            chunks += (p.len + kUnpackChunk - 1) / kUnpackChunk;
+            b.pieces.push_back(p);
+            pos = stop;
+        }
+    }
+    if (chunks > 0x7FFFFFFFull) return false;
+    b.n_chunks = (uint32_t)chunks;
+    return true;
+}
+
+}  // namespace hzp
+
+using namespace hzp;
+
+extern "C" const char *hzp_last_error(void) { return g_err; }
+
+extern "C" hzp_status_t hzp_plan(const hzp_plan_desc_t *d, hzp_plan_t **out)
+{
+    if (!d || !out) return fail(HZP_ERR_INVALID_ARG, "hzp_plan: NULL descriptor or output");
+    *out = nullptr;
+    if (d->n_layers == 0 || !d->tensors_per_layer || !d->tensor_numel)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_plan: need at least one layer and its tensor arrays");
+    const uint32_t A = d->align_elems;
+    if (A < 8 || (A & (A - 1)) != 0)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_plan: align_elems=%u must be a power of two >= 8", A);
+    if (d->z3 == 0 || d->z1 == 0)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_plan: group sizes must be positive");
+    if (d->z1 % d->z3 != 0)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_plan: z3=%u must divide z1=%u", d->z3, d->z1);
+    if (d->z2 != 0 && d->z2 != d->z3)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_plan: z2=%u must be 0 or equal to z3=%u", d->z2, d->z3);
+    uint64_t n_tensors = 0;
+    for (uint32_t l = 0; l < d->n_layers; ++l) {
+        if (d->tensors_per_layer[l] == 0)
+            return fail(HZP_ERR_INVALID_ARG, "hzp_plan: layer %u has no tensor", l);
+        n_tensors += d->tensors_per_layer[l];
+    }
+    if (n_tensors > 0x7FFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_plan: too many tensors");
+    for (uint64_t t = 0; t < n_tensors; ++t) {
+        if (d->tensor_numel[t] == 0)
+            return fail(HZP_ERR_INVALID_ARG, "hzp_plan: tensor %llu is empty", (unsigned long long)t);
+        if (d->tensor_class && d->tensor_class[t] > 1)
+            return fail(HZP_ERR_INVALID_ARG, "hzp_plan: tensor %llu has unknown class %u",
+                        (unsigned long long)t, d->tensor_class[t]);
+    }
+
+    hzp_plan_t *p = new (std::nothrow) hzp_plan_t;
+    if (!p) return fail(HZP_ERR_NOMEM, "hzp_plan: out of host memory");
+    try {
+        p->n_layers = d->n_layers;
+        p->align = A;
+        p->z3 = d->z3;
+        p->z2 = d->z3;
+        p->z1 = d->z1;
+        p->K = d->z1 / d->z3;
+        p->uniform_wd = true;
+        p->tensors.resize(n_tensors);
+        p->bucket_of.assign((size_t)d->n_layers * 2, -1);
+        const uint64_t quantum = (uint64_t)A * d->z1;
+        uint64_t base = 0;
+        uint32_t tid0 = 0, slot = 0, piece_slot = 0;
+        for (uint32_t l = 0; l < d->n_layers; ++l) {
+            const uint32_t cnt = d->tensors_per_layer[l];
+            for (uint32_t cls = 0; cls < 2; ++cls) {
+                BucketRec b{};
+                b.layer = l;
+                b.cls = cls;
+                b.first_slot = slot;
+                uint64_t off = 0, payload_end = 0;
+                for (uint32_t t = tid0; t < tid0 + cnt; ++t) {
+                    const uint32_t c = d->tensor_class ? d->tensor_class[t] : 0u;
+                    if (c != cls) continue;
+                    TensorRec &r = p->tensors[t];
+                    r.layer = l;
+                    r.cls = cls;
+                    r.bucket = (uint32_t)p->buckets.size();
+                    r.index_in_bucket = (uint32_t)b.tensor_ids.size();
+                    r.offset = off;
+                    r.numel = d->tensor_numel[t];
+                    r.wd_mult = d->tensor_wd_mult ? d->tensor_wd_mult[t] : 1.0f;
+                    if (r.wd_mult != 1.0f) p->uniform_wd = false;
+                    if (__builtin_add_overflow(off, r.numel, &payload_end) ||
+                        !round_up(payload_end, A, &off)) {
+                        delete p;
+                        return fail(HZP_ERR_INVALID_ARG, "hzp_plan: layer %u overflows 64 bits", l);
+                    }
+                    b.tensor_ids.push_back(t);
+                }
+                if (b.tensor_ids.empty()) continue;     // no tensor of this class: no bucket
+                b.n_tensors = (uint32_t)b.tensor_ids.size();
+                b.payload_end = payload_end;
+                if (!round_up(payload_end, quantum, &b.P) || __builtin_add_overflow(base, b.P, &base)) {
+                    delete p;
+                    return fail(HZP_ERR_INVALID_ARG, "hzp_plan: layer %u overflows 64 bits", l);
+                }
+                b.base = base - b.P;
+                b.S3 = b.P / d->z3;
+                b.S1 = b.P / d->z1;
+                b.piece_slot = piece_slot;
+                if (!build_pieces(p, b)) {
+                    delete p;
+                    return fail(HZP_ERR_UNSUPPORTED, "hzp_plan: layer %u is too large to unpack", l);
+                }
+                piece_slot += (uint32_t)b.pieces.size();
+                for (uint32_t t : b.tensor_ids) {
+                    p->slot_off.push_back(p->tensors[t].offset);
+                    p->slot_wd.push_back(p->tensors[t].wd_mult);
+                }
+                slot += b.n_tensors;
+                p->bucket_of[(size_t)l * 2 + cls] = (int32_t)p->buckets.size();
+                p->buckets.push_back(std::move(b));
+            }
+            tid0 += cnt;
+        }
+        p->total_padded = base;
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(HZP_ERR_NOMEM, "hzp_plan: out of host memory");
+    }
+    *out = p;
+    return HZP_OK;
+}
+
+extern "C" void hzp_plan_free(hzp_plan_t *plan)
+{
+    if (!plan) return;
+    free_device_tables(plan);
+    delete plan;
+}
+
+extern "C" hzp_status_t hzp_plan_info(const hzp_plan_t *plan, hzp_plan_info_t *o)
+{
+    if (!plan || !o) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_info: NULL argument");
+    o->n_layers = plan->n_layers;
+    o->n_buckets = (uint32_t)plan->buckets.size();
+    o->n_tensors = (uint32_t)plan->tensors.size();
+    o->align_elems = plan->align;
+    o->z3 = plan->z3;
+    o->z2 = plan->z2;
+    o->z1 = plan->z1;
+    o->k = plan->K;
+    o->total_padded = plan->total_padded;
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_plan_bucket(const hzp_plan_t *plan, uint32_t layer, uint32_t cls,
+                                        hzp_bucket_info_t *o)
+{
+    if (!plan || !o) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_bucket: NULL argument");
+    const BucketRec *b = find_bucket(plan, layer, cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_plan_bucket: no bucket (layer %u, class %u)", layer, cls);
+    o->layer = b->layer;
+    o->cls = b->cls;
+    o->n_tensors = b->n_tensors;
+    o->bucket_index = (uint32_t)(b - plan->buckets.data());
+    o->payload_end = b->payload_end;
+    o->padded = b->P;
+    o->s3 = b->S3;
+    o->s1 = b->S1;
+    o->base = b->base;
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_plan_tensor(const hzp_plan_t *plan, uint32_t tensor_id, hzp_tensor_info_t *o)
+{
+    if (!plan || !o) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_tensor: NULL argument");
+    if (tensor_id >= plan->tensors.size())
+        return fail(HZP_ERR_RANGE, "hzp_plan_tensor: tensor %u of %zu", tensor_id, plan->tensors.size());
+    const TensorRec &t = plan->tensors[tensor_id];
+    o->layer = t.layer;
+    o->cls = t.cls;
+    o->bucket_index = t.bucket;
+    o->index_in_bucket = t.index_in_bucket;
+    o->offset = t.offset;
+    o->numel = t.numel;
+    o->wd_mult = t.wd_mult;
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_plan_rank(const hzp_plan_t *plan, uint32_t rank, uint32_t *j, uint32_t *k,
+                                      uint32_t *i)
+{
+    if (!plan) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_rank: NULL plan");
+    if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_plan_rank: rank %u of %u", rank, plan->z1);
+    const uint32_t jj = rank % plan->z3, kk = rank / plan->z3;
+    if (j) *j = jj;
+    if (k) *k = kk;
+    if (i) *i = jj * plan->K + kk;
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_plan_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level,
+                                       uint32_t rank, uint64_t *begin, uint64_t *len)
+{
+    if (!plan || !begin || !len) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_shard: NULL argument");
+    const BucketRec *b = find_bucket(plan, layer, cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_plan_shard: no bucket (layer %u, class %u)", layer, cls);
+    if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_plan_shard: rank %u of %u", rank, plan->z1);
+    const uint64_t j = rank % plan->z3, k = rank / plan->z3;
+    if (level == 3) {
+        *begin = j * b->S3;
+        *len = b->S3;
+    } else if (level == 1) {
+        *begin = (j * plan->K + k) * b->S1;
+        *len = b->S1;
+    } else {
+        return fail(HZP_ERR_RANGE, "hzp_plan_shard: level %d is neither 1 nor 3", level);
+    }
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt, uint64_t *grad, uint64_t *par)
+{
+    if (!plan) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_bytes: NULL plan");
+    uint64_t o = 0, g = 0, q = 0;
+    for (const BucketRec &b : plan->buckets) {
+        o += 12 * b.S1;
+        g += 4 * (b.P / plan->z2);
+        q += (b.cls == HZP_CLASS_F32 ? 4 : 2) * b.S3;
+    }
+    if (opt) *opt = o;
+    if (grad) *grad = g;
+    if (par) *par = q;
+    return HZP_OK;
+}

@@ -1,0 +1,77 @@
+"""The library's planner against the layout oracle, bit for bit (runs without a GPU)."""
+from hypothesis import given, settings, strategies as st
+
+import hzp_inputs
+import paper_2510_20111_amd as hzp
+from oracle import planner as op
+
+
+def _compare(d):
+    want = op.make_plan(d["tensors_per_layer"], d["tensor_numel"], d["align"], d["z3"], d["z1"],
+                        tensor_class=d.get("tensor_class"), tensor_wd_mult=d.get("tensor_wd_mult"))
+    got = hzp.hzp_plan(d["tensors_per_layer"], d["tensor_numel"], d["align"], d["z3"], d["z1"],
+                       tensor_class=d.get("tensor_class"), tensor_wd_mult=d.get("tensor_wd_mult"))
+    info = got.info()
+    assert (info.n_layers, info.n_buckets, info.n_tensors) == (
+        want["n_layers"], len(want["buckets"]), len(want["tensors"]))
+    assert (info.align_elems, info.z3, info.z2, info.z1, info.k, info.total_padded) == (
+        want["align"], want["z3"], want["z2"], want["z1"], want["K"], want["total_padded"])
+    for layer in range(want["n_layers"]):
+        for cls in (0, 1):
+            wb = op.find_bucket(want, layer, cls)
+            assert got.has_bucket(layer, cls) == (wb is not None)
+    for idx, wb in enumerate(want["buckets"]):
+        gb = got.bucket(wb["layer"], wb["cls"])
+        assert (gb.layer, gb.cls, gb.n_tensors, gb.bucket_index, gb.payload_end, gb.padded, gb.s3,
+                gb.s1, gb.base) == (wb["layer"], wb["cls"], len(wb["tensor_ids"]), idx,
+                                    wb["payload_end"], wb["P"], wb["S3"], wb["S1"], wb["base"])
+        ranks = range(want["z1"]) if want["z1"] <= 16 else [0, 1, want["z3"], want["z1"] - 1]
+        for rank in ranks:
+            for level in (1, 3):
+                assert got.shard(wb["layer"], wb["cls"], level, rank) == \
+                    op.shard_range(want, wb, level, rank)
+    ranks = range(want["z1"]) if want["z1"] <= 64 else [0, 1, 7, 8, want["z1"] - 1]
+    for rank in ranks:
+        assert got.rank(rank) == op.rank_to_indices(want, rank)
+    tensor_ids = range(len(want["tensors"])) if len(want["tensors"]) <= 300 else \
+        list(range(0, len(want["tensors"]), 37)) + [len(want["tensors"]) - 1]
+    for t in tensor_ids:
+        wt, gt = want["tensors"][t], got.tensor(t)
+        assert (gt.layer, gt.cls, gt.bucket_index, gt.offset, gt.numel, gt.wd_mult) == (
+            wt["layer"], wt["cls"], wt["bucket"], wt["offset"], wt["numel"], wt["wd_mult"])
+        assert want["buckets"][wt["bucket"]]["tensor_ids"][gt.index_in_bucket] == t
+    assert got.bytes() == op.per_rank_bytes(want)
+
+
+@st.composite
+def descriptors(draw):
+    n_layers = draw(st.integers(1, 5))
+    tpl = [draw(st.integers(1, 6)) for _ in range(n_layers)]
+    n = sum(tpl)
+    numel = [draw(st.one_of(st.integers(1, 400), st.integers(1, 100000))) for _ in range(n)]
+    cls = draw(st.one_of(st.none(), st.lists(st.integers(0, 1), min_size=n, max_size=n)))
+    wd = draw(st.one_of(st.none(), st.lists(st.sampled_from([0.0, 1.0, 0.5]), min_size=n, max_size=n)))
+    align = draw(st.sampled_from([8, 16, 64, 128, 256]))
+    z3 = draw(st.sampled_from([1, 2, 3, 4, 8]))
+    K = draw(st.sampled_from([1, 2, 4, 5, 16]))
+    return dict(tensors_per_layer=tpl, tensor_numel=numel, tensor_class=cls, tensor_wd_mult=wd,
+                align=align, z3=z3, z1=z3 * K)
+
+
+@settings(max_examples=150, deadline=None)
+@given(descriptors())
+def test_random_descriptors(d):
+    _compare(d)
+
+
+def test_the_five_workloads():
+    for idx in range(5):
+        _compare(hzp_inputs.config(idx))
+
+
+def test_paper_group_sizes():
+    """Z1 = 64 and 256 with Z2 = Z3 = 8, the settings of the paper's experiments (Tables 2-5)."""
+    c = hzp_inputs.config(1)
+    for z1 in (64, 256):
+        _compare(dict(c, z1=z1, tensors_per_layer=c["tensors_per_layer"][:3],
+                      tensor_numel=c["tensor_numel"][:27]))
