@@ -70,6 +70,10 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError("libhzp.so is not built: run `python paper_2510_20111_amd/build.py` "
                           "(or __graft_entry__.build()) first; there is no fallback path")
+    # torch ships its own HIP runtime (same soname as the system one).  Loading torch first
+    # makes libhzp bind to that copy, so both share one runtime, one device context and the
+    # same streams; two runtimes in one process cannot both open the GPU.
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, u32, u64p = ctypes.c_void_p, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint64)
     u32p = ctypes.POINTER(ctypes.c_uint32)
