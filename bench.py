@@ -1,0 +1,283 @@
+#!/usr/bin/env python3
+"""Benchmark of the one-GPU share of the AsyncHZP data-parallel hot path on MI355X.
+
+A step is one pass of the whole path over one rank's share of a model-shaped state:
+  1. fused gradient reduction (R bf16 contributions, fp32 sum) + AdamW + bf16 cast on the rank's
+     ZeRO-1 shard of every layer bucket            (one hzp_adamw_shard call over the layer range)
+  2. level-1 gather: K owners' bf16 outputs -> the ZeRO-3 parameter shard, per bucket
+  3. level-3 gather: Z3 parameter shards -> the full padded layer bucket, per bucket
+The layout plan is built once before the loop (it is static).  All inputs are synthetic, seeded
+and resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="workload index 0..4 (1 = 7B-class dense)")
+    ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--phases", default="fused,gather1,gather3",
+                    help="comma list of the step's phases to run (profiling aid)")
+    return ap.parse_args()
+
+
+class Workload:
+    """Device buffers and pre-marshalled pointer arrays of one rank's share."""
+
+    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs):
+        self.cfg, self.rank = cfg, rank
+        dev = "cuda:0"
+        tpl = cfg["tensors_per_layer"][:n_layers]
+        numel = cfg["tensor_numel"][:sum(tpl)]
+        self.plan = hzp.hzp_plan(tpl, numel, cfg["align"], cfg["z3"], cfg["z1"])
+        info = self.plan.info()
+        self.n_layers, self.R, self.K, self.z3 = n_layers, cfg["R"], info.k, info.z3
+        self.buckets = [self.plan.bucket(l, 0) for l in range(n_layers)]
+        self.s1_total = sum(b.s1 for b in self.buckets)
+        self.s3_total = sum(b.s3 for b in self.buckets)
+        self.p_total = sum(b.padded for b in self.buckets)
+        j, k, i = self.plan.rank(rank)
+        self.keep = []
+        g_ptrs, p_ptrs, m_ptrs, v_ptrs, o_ptrs = [], [], [], [], []
+        self.l1_args, self.l3_args = [], []
+        tid = 0
+        for l, b in enumerate(self.buckets):
+            ranges = []
+            for _ in range(b.n_tensors):
+                t = self.plan.tensor(tid)
+                ranges.append((t.offset, t.numel))
+                tid += 1
+            beg, n = self.plan.shard(l, 0, 1, rank)
+            pad = None if b.payload_end == b.padded else ranges
+            grads = [hzp_inputs.device_normal(n, cfg["sigma"], 1000003 * l + 17 * r + 1, dev,
+                                              torch.bfloat16, pad, beg) for r in range(self.R)]
+            p = hzp_inputs.device_normal(n, 0.02, 1000003 * l + 7919, dev, torch.float32, pad, beg)
+            m = torch.zeros(n, dtype=torch.float32, device=dev)
+            v = torch.zeros(n, dtype=torch.float32, device=dev)
+            out = torch.empty(n, dtype=torch.bfloat16, device=dev)
+            # level 1: this rank's output is owner k; the other K-1 owners' pieces are "received"
+            owners = [out if kk == k else torch.randn(n, device=dev).to(torch.bfloat16) for kk in range(self.K)]
+            shard3 = torch.empty(b.s3, dtype=torch.bfloat16, device=dev)
+            # level 3: this rank's shard is j; the other Z3-1 shards are "received"
+            shards = [shard3 if jj == j else torch.randn(b.s3, device=dev).to(torch.bfloat16)
+                      for jj in range(self.z3)]
+            bucket = torch.empty(b.padded, dtype=torch.bfloat16, device=dev)
+            self.keep.append((grads, p, m, v, out, owners, shard3, shards, bucket))
+            g_ptrs += grads
+            p_ptrs.append(p); m_ptrs.append(m); v_ptrs.append(v); o_ptrs.append(out)
+            self.l1_args.append((l, hzp.ptr_array(owners), shard3.data_ptr()))
+            self.l3_args.append((l, hzp.ptr_array(shards), bucket.data_ptr()))
+        self.g_arr, self.p_arr = hzp.ptr_array(g_ptrs), hzp.ptr_array(p_ptrs)
+        self.m_arr, self.v_arr, self.o_arr = hzp.ptr_array(m_ptrs), hzp.ptr_array(v_ptrs), hzp.ptr_array(o_ptrs)
+
+
+def run_step(w, hzp, step, stream, phases, events=None):
+    a = w.cfg["adamw"]
+    hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"],
+                         w.cfg["grad_scale"], step)
+    s = stream.cuda_stream
+    if events:
+        events[0].record(stream)
+    if "fused" in phases:
+        hzp.hzp_adamw_shard(w.plan, 0, w.n_layers, 0, w.rank, hy, w.g_arr, w.R, w.p_arr, w.m_arr,
+                            w.v_arr, w.o_arr, stream=s)
+    if events:
+        events[1].record(stream)
+    if "gather1" in phases:
+        for l, arr, dst in w.l1_args:
+            hzp.hzp_gather_layer(w.plan, l, 0, 1, arr, dst, None, stream=s)
+    if events:
+        events[2].record(stream)
+    if "gather3" in phases:
+        for l, arr, dst in w.l3_args:
+            hzp.hzp_gather_layer(w.plan, l, 0, 3, arr, dst, None, stream=s)
+    if events:
+        events[3].record(stream)
+
+
+def copy_probe(torch, hzp, stream):
+    """Achievable-bandwidth context: the library's own concat kernel used as a plain copy
+    (Z3 = 1) on 1 GiB, and torch's device-to-device copy of the same buffers."""
+    n = 1 << 29     # bf16 elements = 1 GiB
+    plan = hzp.hzp_plan([1], [n], 8, 1, 1)
+    src = torch.empty(n, dtype=torch.bfloat16, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    out = {}
+    for name, fn in (("hzp_concat_copy", lambda: hzp.hzp_gather_layer(plan, 0, 0, 3, [src], dst, None,
+                                                                        stream=stream.cuda_stream)),
+                     ("torch_copy", lambda: dst.copy_(src))):
+        with torch.cuda.stream(stream):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                fn()
+            e1.record(stream)
+        stream.synchronize()
+        out[name + "_GBps"] = round(2 * n * 2 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    return out
+
+
+def cpu_baseline(w, torch, np):
+    """The oracle, as it stands, on one layer's share of the same workload: reduce + AdamW on
+    the S1 shard, then both gathers for that layer; repeated for roughly 15 s."""
+    from oracle import numeric as on
+    grads, p, m, v, out, owners, shard3, shards, bucket = w.keep[0]
+    a = w.cfg["adamw"]
+
+    def host16(t):
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    g_h = [host16(g) for g in grads]
+    p_h, m_h, v_h = p.cpu().numpy().copy(), m.cpu().numpy().copy(), v.cpu().numpy().copy()
+    owners_h = [host16(o) for o in owners]
+    shards_h = [host16(s) for s in shards]
+    n = p_h.size
+
+    def one_pass(step):
+        g = on.reduce(g_h, scale=w.cfg["grad_scale"])
+        o16 = on.adamw(g, p_h, m_h, v_h, step=step, **a)
+        k = w.plan.rank(w.rank)[1]
+        j = w.plan.rank(w.rank)[0]
+        s3 = on.gather_concat([o16 if kk == k else owners_h[kk] for kk in range(w.K)])
+        on.gather_concat([s3 if jj == j else shards_h[jj] for jj in range(w.z3)])
+
+    t0 = time.perf_counter()
+    one_pass(1)
+    first = time.perf_counter() - t0
+    reps = max(1, min(20, int(15.0 / max(first, 1e-3))))
+    t0 = time.perf_counter()
+    for r in range(reps):
+        one_pass(2 + r)
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": n / dt, "unit": "params/s", "cores": on.threads(), "kind": "oracle",
+            "sample": "layer 0 of the same workload: fp32 reduce of R=%d bf16 slices + fp64 AdamW on its "
+                      "S1=%d shard, level-1 and level-3 gather of that layer; %d passes, %.2f s each"
+                      % (w.R, n, reps, dt)}
+
+
+def read_traffic(kernel_key):
+    """HBM bytes per launch of a kernel as measured with rocprofv3 counters (committed summary)."""
+    path = os.path.join(ROOT, "profiles", "traffic_bytes_per_launch.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split("#")[0].split()
+                if len(parts) >= 2 and parts[0] == kernel_key:
+                    return float(parts[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build covers the one-GPU share of the path only; replicas are buffers in one "
+              "GPU's HBM and no collective is issued, so --gpus must be 1 (got %d)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import hzp_inputs
+    import paper_2510_20111_amd as hzp
+
+    torch.cuda.set_device(0)
+    cfg = hzp_inputs.config(args.config)
+    n_layers = len(cfg["tensors_per_layer"]) if args.layers <= 0 else min(args.layers, len(cfg["tensors_per_layer"]))
+    rank = cfg["z3"] + 1 if cfg["z1"] > cfg["z3"] + 1 else 0      # a rank with j = 1, k = 1
+    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs)
+    phases = set(args.phases.split(","))
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    step = 0
+    for _ in range(args.warmup):
+        step += 1
+        run_step(w, hzp, step, stream, phases)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step += 1
+        run_step(w, hzp, step, stream, phases, evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    ph = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in evs])     # ms
+    fused_ms, g1_ms, g3_ms = (float(x) for x in ph.mean(axis=0))
+    R = w.R
+    fused_bytes = (26 + 2 * R) * w.s1_total
+    g1_bytes, g3_bytes = 4 * w.s3_total, 4 * w.p_total
+
+    def roof(kernel, algo_bytes, ms, launches, key):
+        per_launch_ms = ms / launches
+        ach = algo_bytes / launches / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        return {"kernel": kernel, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": read_traffic(key),
+                "launches_per_step": launches, "avg_launch_us": round(per_launch_ms * 1e3, 2),
+                "algorithmic_bytes_per_launch": algo_bytes / launches,
+                "share_of_step_time": round(ms / max(fused_ms + g1_ms + g3_ms, 1e-9), 3)}
+
+    segs_per_launch = min(34, 408 // (R + 4))        # capacity of the kernel-argument segment table
+    fused_launches = -(-w.n_layers // segs_per_launch)
+    rooflines = {}
+    if "fused" in phases:
+        rooflines["fused_adamw"] = roof("fused_adamw_kernel<R=%d,bf16>" % R, fused_bytes, fused_ms,
+                                        fused_launches, "fused_adamw_%s" % cfg["name"])
+    if "gather1" in phases:
+        rooflines["gather_level1"] = roof("concat_kernel (K=%d x S1 -> S3)" % w.K, g1_bytes, g1_ms,
+                                          w.n_layers, "concat_l1_%s" % cfg["name"])
+    if "gather3" in phases:
+        rooflines["gather_level3"] = roof("concat_kernel (Z3=%d x S3 -> P)" % w.z3, g3_bytes, g3_ms,
+                                          w.n_layers, "concat_l3_%s" % cfg["name"])
+    dominant = max(rooflines.values(), key=lambda r: r["share_of_step_time"])
+
+    result = {
+        "metric": "fused reduce+AdamW shard update: params/sec and achieved HBM GB/s (% of peak)",
+        "value": w.s1_total / (ms_per_step * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d layer buckets, R=%d, Z3=%d, Z1=%d, A=%d, rank %d; step = fused "
+                               "reduce+AdamW on the S1 shards + level-1 gather + level-3 gather"
+                               % (cfg["name"], w.n_layers, R, w.z3, cfg["z1"], cfg["align"], rank),
+                   "shard_params_per_step": w.s1_total, "padded_params": w.p_total,
+                   "phases": sorted(phases)},
+        "roofline": dominant,
+        "rooflines": rooflines,
+        "fused_update": {"params_per_s": w.s1_total / (fused_ms * 1e-3) if fused_ms > 0 else None,
+                         "GBps": rooflines.get("fused_adamw", {}).get("achieved"),
+                         "bytes_per_param": 26 + 2 * R, "ms": round(fused_ms, 4)},
+        "phase_ms": {"fused": round(fused_ms, 4), "gather_level1": round(g1_ms, 4),
+                     "gather_level3": round(g3_ms, 4)},
+    }
+    if not args.no_probe:
+        result["hbm_probe"] = copy_probe(torch, hzp, stream)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, torch, np)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
