@@ -31,15 +31,23 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--separate-allocations", action="store_true",
+                    help="give every slice its own allocation instead of per-kind arenas (layout experiment)")
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     return ap.parse_args()
 
 
 class Workload:
-    """Device buffers and pre-marshalled pointer arrays of one rank's share."""
+    """Device buffers and pre-marshalled pointer arrays of one rank's share.
 
-    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs):
+    Layout: one arena per stream kind (replica r's gradient slices, master, momentum, variance,
+    bf16 output, received ZeRO-1 pieces, ZeRO-3 shards, received shards, layer buckets), each
+    holding the slices of all layer buckets back to back in bucket order -- the offset of a
+    bucket's slice is the plan's `base` divided by the group size.  `separate=True` gives every
+    slice its own allocation instead (a layout experiment: it streams about 4 % slower)."""
+
+    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False):
         self.cfg, self.rank = cfg, rank
         dev = "cuda:0"
         tpl = cfg["tensors_per_layer"][:n_layers]
@@ -51,7 +59,23 @@ class Workload:
         self.s1_total = sum(b.s1 for b in self.buckets)
         self.s3_total = sum(b.s3 for b in self.buckets)
         self.p_total = sum(b.padded for b in self.buckets)
+        assert self.p_total == info.total_padded
         j, k, i = self.plan.rank(rank)
+        bf16, f32 = torch.bfloat16, torch.float32
+        arenas = {}
+
+        def arena(name, total, dtype):
+            if name not in arenas:
+                arenas[name] = torch.empty(total, dtype=dtype, device=dev)
+            return arenas[name]
+
+        def piece(name, total, dtype, begin, n, fill=None):
+            """Slice [begin, begin+n) of the arena `name`, or an allocation of its own."""
+            t = torch.empty(n, dtype=dtype, device=dev) if separate else arena(name, total, dtype)[begin:begin + n]
+            if fill is not None:
+                t.copy_(fill)
+            return t
+
         self.keep = []
         g_ptrs, p_ptrs, m_ptrs, v_ptrs, o_ptrs = [], [], [], [], []
         self.l1_args, self.l3_args = [], []
@@ -63,25 +87,30 @@ class Workload:
                 ranges.append((t.offset, t.numel))
                 tid += 1
             beg, n = self.plan.shard(l, 0, 1, rank)
+            o1, o3 = b.base // cfg["z1"], b.base // cfg["z3"]       # arena offsets of this bucket's slices
             pad = None if b.payload_end == b.padded else ranges
-            grads = [hzp_inputs.device_normal(n, cfg["sigma"], 1000003 * l + 17 * r + 1, dev,
-                                              torch.bfloat16, pad, beg) for r in range(self.R)]
-            p = hzp_inputs.device_normal(n, 0.02, 1000003 * l + 7919, dev, torch.float32, pad, beg)
-            m = torch.zeros(n, dtype=torch.float32, device=dev)
-            v = torch.zeros(n, dtype=torch.float32, device=dev)
-            out = torch.empty(n, dtype=torch.bfloat16, device=dev)
+            grads = [piece("g%d" % r, self.s1_total, bf16, o1, n,
+                           hzp_inputs.device_normal(n, cfg["sigma"], 1000003 * l + 17 * r + 1, dev, bf16, pad, beg))
+                     for r in range(self.R)]
+            p = piece("p", self.s1_total, f32, o1, n,
+                      hzp_inputs.device_normal(n, 0.02, 1000003 * l + 7919, dev, f32, pad, beg))
+            m = piece("m", self.s1_total, f32, o1, n).zero_()
+            v = piece("v", self.s1_total, f32, o1, n).zero_()
+            out = piece("o", self.s1_total, bf16, o1, n).zero_()
             # level 1: this rank's output is owner k; the other K-1 owners' pieces are "received"
-            owners = [out if kk == k else torch.randn(n, device=dev).to(torch.bfloat16) for kk in range(self.K)]
-            shard3 = torch.empty(b.s3, dtype=torch.bfloat16, device=dev)
+            owners = [out if kk == k else piece("recv1_%d" % kk, self.s1_total, bf16, o1, n).normal_()
+                      for kk in range(self.K)]
+            shard3 = piece("s3", self.s3_total, bf16, o3, b.s3).zero_()
             # level 3: this rank's shard is j; the other Z3-1 shards are "received"
-            shards = [shard3 if jj == j else torch.randn(b.s3, device=dev).to(torch.bfloat16)
+            shards = [shard3 if jj == j else piece("recv3_%d" % jj, self.s3_total, bf16, o3, b.s3).normal_()
                       for jj in range(self.z3)]
-            bucket = torch.empty(b.padded, dtype=torch.bfloat16, device=dev)
+            bucket = piece("bucket", self.p_total, bf16, b.base, b.padded)
             self.keep.append((grads, p, m, v, out, owners, shard3, shards, bucket))
             g_ptrs += grads
             p_ptrs.append(p); m_ptrs.append(m); v_ptrs.append(v); o_ptrs.append(out)
             self.l1_args.append((l, hzp.ptr_array(owners), shard3.data_ptr()))
             self.l3_args.append((l, hzp.ptr_array(shards), bucket.data_ptr()))
+        self.arenas = arenas
         self.g_arr, self.p_arr = hzp.ptr_array(g_ptrs), hzp.ptr_array(p_ptrs)
         self.m_arr, self.v_arr, self.o_arr = hzp.ptr_array(m_ptrs), hzp.ptr_array(v_ptrs), hzp.ptr_array(o_ptrs)
 
@@ -202,7 +231,7 @@ def main():
     cfg = hzp_inputs.config(args.config)
     n_layers = len(cfg["tensors_per_layer"]) if args.layers <= 0 else min(args.layers, len(cfg["tensors_per_layer"]))
     rank = cfg["z3"] + 1 if cfg["z1"] > cfg["z3"] + 1 else 0      # a rank with j = 1, k = 1
-    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs)
+    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations)
     phases = set(args.phases.split(","))
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()

@@ -156,7 +156,7 @@ hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt_bytes, uint64_
  *   R           : 1 .. HZP_MAX_REPLICAS
  *   out_f32     : device pointer, n floats, 16-byte aligned; read first when accumulate != 0;
  *                 must not overlap any input
- * Errors: INVALID_ARG, RANGE (layer / class / level / rank), UNSUPPORTED (R too large), ALIGN, HIP.
+ * Errors: INVALID_ARG, RANGE (layer / class / level / rank), UNSUPPORTED (R too large, or a shard of 2^30 elements or more), ALIGN, HIP.
  * ------------------------------------------------------------------------------------------ */
 hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level, uint32_t rank,
                               const void *const *grad_slices, uint32_t R, float scale, int accumulate,
@@ -187,7 +187,7 @@ hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t c
  *   param_out   : device pointers to S1 bf16 (class BF16) or S1 floats (class F32), 16-byte
  *                 aligned; the array itself may be NULL (no cast output)
  * No buffer may overlap another.  step is 1-based.
- * Errors: INVALID_ARG (NULL, step 0, empty range), RANGE, UNSUPPORTED (R too large), ALIGN, HIP.
+ * Errors: INVALID_ARG (NULL, step 0, empty range), RANGE, UNSUPPORTED (R too large, or a shard of 2^30 elements or more), ALIGN, HIP.
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay, grad_scale;

@@ -30,7 +30,7 @@ extern "C" hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer,
     if (R > HZP_MAX_REPLICAS)
         return fail(HZP_ERR_UNSUPPORTED, "hzp_reduce_shard: R=%u exceeds %u", R, HZP_MAX_REPLICAS);
     const uint64_t n = level == 1 ? b->S1 : b->S3;
-    if (n / 4 > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_reduce_shard: shard too large");
+    if (n >= (1ull << 30)) return fail(HZP_ERR_UNSUPPORTED, "hzp_reduce_shard: shard of 2^30 elements or more");
     for (uint32_t r = 0; r < R; ++r) {
         if (!grad_slices[r]) return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: slice %u is NULL", r);
         if (!aligned16(grad_slices[r]))
@@ -83,7 +83,8 @@ extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_b
         f.first_slot = b->first_slot;
         f.n_tensors = b->n_tensors;
         f.shard_begin = (j * plan->K + k) * b->S1;
-        if (f.n / 4 > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: shard too large");
+        if (f.n >= (1ull << 30))
+            return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: layer %u: shard of 2^30 elements or more", layer);
         if (!f.master || !f.m || !f.v)
             return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: layer %u: NULL state pointer", layer);
         if (!aligned16(f.master) || !aligned16(f.m) || !aligned16(f.v) || !aligned16(f.out))

@@ -64,12 +64,30 @@ def bf16_ulp_distance(a, b):
     return np.abs(key(a) - key(b))
 
 
-def assert_bf16_within_one_ulp(got, want, what):
+def assert_bf16_within_one_ulp(got, want, what, p_ref=None):
+    """Cast parameters: at most one bf16 ulp from the oracle's cast parameters.
+
+    An element far below the array's RMS is judged like the fp32 parameter it is the cast of:
+    there the fp32 tolerance (REL_TOL * rms, see assert_close_f32) is wider than a bf16 ulp of the
+    element, so two correct fp32 values may round to bf16 values several ulps apart.  With
+    `p_ref` (the oracle's fp32 parameters) such an element passes if its value is within one
+    bf16 ulp plus that fp32 tolerance of the oracle's."""
     nan_w = (want & 0x7F80 == 0x7F80) & (want & 0x007F != 0)
     nan_g = (got & 0x7F80 == 0x7F80) & (got & 0x007F != 0)
     assert np.array_equal(nan_g, nan_w), what + ": NaN pattern differs"
-    d = bf16_ulp_distance(got[~nan_w], want[~nan_w])
-    assert d.size == 0 or d.max() <= 1, "%s: bf16 distance %d ulp" % (what, int(d.max()))
+    d = bf16_ulp_distance(got, want)
+    d[nan_w] = 0
+    bad = d > 1
+    if bad.any() and p_ref is not None:
+        p64 = p_ref.astype(np.float64)
+        p64 = p64[np.isfinite(p64)]
+        floor = REL_TOL * math.sqrt(float(np.mean(p64 * p64))) if p64.size else 0.0
+        val = lambda u: (u.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        w = want[bad]
+        ulp = np.abs(val(w + np.uint16(1)) - val(w))
+        bad[bad] = np.abs(val(got[bad]) - val(w)) > ulp + floor
+    assert not bad.any(), "%s: %d elements more than one bf16 ulp away (worst %d)" % (
+        what, int(bad.sum()), int(d[bad].max()))
 
 
 def payload_ranges(oplan, bucket):

@@ -180,7 +180,7 @@ class Sim:
                 assert guards_intact(dv[key][0], n), tag + " guard " + key
             if with_out:
                 if b["cls"] == 0:
-                    assert_bf16_within_one_ulp(to_host(dv["out"][1], np.uint16), st["out"], tag + " bf16")
+                    assert_bf16_within_one_ulp(to_host(dv["out"][1], np.uint16), st["out"], tag + " bf16", st["p"])
                 else:
                     got = to_host(dv["out"][1], np.float32)
                     assert np.array_equal(got.view(np.uint32), to_host(dv["p"][1], np.uint32)), tag + " fp32 copy"
@@ -219,7 +219,8 @@ def test_tiny_workload_ten_steps_every_rank():
         torch.cuda.synchronize()
         want_shards1 = [sim.o[bi, op_rank_of_shard(oplan, i)]["out"] for i in range(oplan["z1"])]
         want_full = np.concatenate(want_shards1)
-        assert_bf16_within_one_ulp(to_host(full, np.uint16), want_full, "gathered bucket %d" % bi)
+        want_p = np.concatenate([sim.o[bi, op_rank_of_shard(oplan, i)]["p"] for i in range(oplan["z1"])])
+        assert_bf16_within_one_ulp(to_host(full, np.uint16), want_full, "gathered bucket %d" % bi, want_p)
         for t, tout in zip(b["tensor_ids"], touts):
             rec = oplan["tensors"][t]
             assert np.array_equal(to_host(tout, np.uint16),
@@ -281,7 +282,7 @@ def test_prereduced_fp32_gradient_form():
         want16 = on.adamw(g, h["p"], h["m"], h["v"], step=3, **HP)
         for key in ("p", "m", "v"):
             assert_close_f32(to_host(dev[l][key], np.float32), h[key], "layer %d %s" % (l, key))
-        assert_bf16_within_one_ulp(to_host(outs[l], np.uint16), want16, "layer %d bf16" % l)
+        assert_bf16_within_one_ulp(to_host(outs[l], np.uint16), want16, "layer %d bf16" % l, h["p"])
 
 
 def test_cast_is_round_to_nearest_even_exhaustively():
@@ -363,7 +364,7 @@ def test_side_stream_and_layer_subrange():
         if layer in (1, 2):
             want16 = on.adamw(on.reduce(h["g"], scale=0.5), h["p"], h["m"], h["v"], step=1, **HP)
             assert_close_f32(to_host(d["p"], np.float32), h["p"], "layer %d p" % layer)
-            assert_bf16_within_one_ulp(to_host(d["out"], np.uint16), want16, "layer %d bf16" % layer)
+            assert_bf16_within_one_ulp(to_host(d["out"], np.uint16), want16, "layer %d bf16" % layer, h["p"])
         else:
             assert np.array_equal(to_host(d["p"], np.uint32), h["p"].view(np.uint32))
             assert not to_host(d["out"], np.uint16).any()
