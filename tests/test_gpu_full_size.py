@@ -1,0 +1,154 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times
+(its Workload arenas and its run_step): sampled elements are recomputed one by one by the oracle,
+and whole outputs are checked through properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+import bench
+import hzp_inputs
+import paper_2510_20111_amd as hzp
+from oracle import numeric as on
+from oracle import planner as op
+
+from gpu_util import (DEV, assert_bf16_within_one_ulp, assert_close_f32, oracle_plan, to_dev, to_host)
+from test_gpu_parity import Sim, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits16(t):
+    return t.view(torch.int16)
+
+
+def _sample_indices(n, rng, count=4096, edge=1024):
+    edge = min(edge, n // 2)
+    idx = np.concatenate([np.arange(edge), np.arange(n - edge, n), rng.integers(0, n, size=count)])
+    return np.unique(idx)
+
+
+def _fused_sampled_parity(cfg_idx, n_layers, steps=2):
+    cfg = hzp_inputs.config(cfg_idx)
+    rank = cfg["z3"] + 1
+    w = bench.Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs)
+    stream = torch.cuda.Stream()
+    rng = np.random.default_rng(100 + cfg_idx)
+    a = cfg["adamw"]
+    samples = []
+    for l, (grads, p, m, v, out, owners, shard3, shards, bucket) in enumerate(w.keep):
+        idx = _sample_indices(p.numel(), rng)
+        ti = torch.from_numpy(idx).to(DEV)
+        samples.append(dict(idx=idx, ti=ti,
+                            g=[to_host(_bits16(g)[ti], np.uint16) for g in grads],
+                            p=to_host(p[ti], np.float32).copy(), m=to_host(m[ti], np.float32).copy(),
+                            v=to_host(v[ti], np.float32).copy()))
+    torch.cuda.synchronize()
+    for step in range(1, steps + 1):
+        say("workload %s: step %d over %d buckets, %d shard elements" % (cfg["name"], step, n_layers, w.s1_total))
+        bench.run_step(w, hzp, step, stream, {"fused", "gather1", "gather3"})
+        stream.synchronize()
+        for l, s in enumerate(samples):
+            grads, p, m, v, out, owners, shard3, shards, bucket = w.keep[l]
+            g = on.reduce(s["g"], scale=cfg["grad_scale"])
+            want16 = on.adamw(g, s["p"], s["m"], s["v"], step=step, **a)
+            tag = "%s bucket %d step %d" % (cfg["name"], l, step)
+            for key, t in (("p", p), ("m", m), ("v", v)):
+                assert_close_f32(to_host(t[s["ti"]], np.float32), s[key], tag + " " + key)
+            assert_bf16_within_one_ulp(to_host(_bits16(out)[s["ti"]], np.uint16), want16, tag + " bf16", s["p"])
+    # gathers: whole-output properties on the device, plus oracle-computed windows at every seam
+    j, k, _ = w.plan.rank(rank)
+    for l, (grads, p, m, v, out, owners, shard3, shards, bucket) in enumerate(w.keep):
+        b = w.buckets[l]
+        assert torch.equal(_bits16(shard3), torch.cat([_bits16(o) for o in owners])), "level 1, bucket %d" % l
+        assert torch.equal(_bits16(bucket), torch.cat([_bits16(s) for s in shards])), "level 3, bucket %d" % l
+        for pieces, dst, ln in ((owners, shard3, b.s1), (shards, bucket, b.s3)):
+            win = min(64, ln)
+            for q in range(1, len(pieces)):
+                tail = to_host(_bits16(pieces[q - 1])[ln - win:], np.uint16).copy()
+                head = to_host(_bits16(pieces[q])[:win], np.uint16).copy()
+                want = on.gather_concat([tail, head])
+                got = to_host(_bits16(dst)[q * ln - win:q * ln + win], np.uint16)
+                assert np.array_equal(got, want), "seam %d of bucket %d" % (q, l)
+    return w
+
+
+def test_dense7b_rank_share_as_benchmarked():
+    """The workload bench.py times: 34 buckets in one fused launch, both gather levels."""
+    w = _fused_sampled_parity(1, 34)
+    assert w.s1_total == 32 * 3162240 + 2048000 + 2048128
+
+
+def test_dense70b_layer_stream_sampled():
+    w = _fused_sampled_parity(2, 3)
+    assert w.buckets[0].s1 == 6684800 and w.buckets[0].padded == 855654400
+
+
+def test_moe_layer_sampled_and_unpacked():
+    """One MoE layer: S1 = 71.4M elements at R = 16, then unpack into its 199 tensors."""
+    w = _fused_sampled_parity(3, 1, steps=1)
+    b = w.buckets[0]
+    assert b.s1 == 71385088 and b.n_tensors == 199
+    grads, p, m, v, out, owners, shard3, shards, bucket = w.keep[0]
+    pool = torch.zeros(int(b.payload_end) + 8, dtype=torch.int16, device=DEV)
+    views, pos = [], 3                      # element-aligned only
+    recs = [w.plan.tensor(t) for t in range(199)]
+    for rec in recs:
+        views.append(pool[pos:pos + rec.numel])
+        pos += rec.numel
+    hzp.hzp_gather_layer(w.plan, 0, 0, 3, shards, None, views)
+    torch.cuda.synchronize()
+    bb = _bits16(bucket)
+    for rec, view in zip(recs, views):
+        assert torch.equal(view, bb[rec.offset:rec.offset + rec.numel]), rec.offset
+    # oracle on sampled windows of three tensors (first, one that straddles a shard seam, last)
+    s3 = int(b.s3)
+    host_shards = [to_host(_bits16(s), np.uint16) for s in shards]
+    straddlers = [r for r in recs if r.offset // s3 != (r.offset + r.numel - 1) // s3]
+    assert straddlers
+    for rec in [recs[0], straddlers[0], recs[-1]]:
+        tid = recs.index(rec)
+        seam = (rec.offset // s3 + 1) * s3 - rec.offset - 40       # 40 elements before a shard seam
+        for start in (0, seam, rec.numel - 80):
+            start = int(min(max(start, 0), rec.numel - 80))
+            want = on.unpack_tensor(host_shards, int(rec.offset) + start, 80)
+            got = to_host(views[tid][start:start + 80], np.uint16)
+            assert np.array_equal(got, want), (tid, start)
+    assert not to_host(pool[:3], np.uint16).any() and not to_host(pool[pos:], np.uint16).any()
+
+
+def test_irregular_4096_tensors_full():
+    """The irregular stress workload in full: 64 groups x (bf16 + fp32 bucket), per-tensor decay
+    multipliers, R = 16, one rank, two steps, every element compared; then all 4096 tensors are
+    unpacked to element-aligned buffers and compared with the oracle bit for bit."""
+    cfg = hzp_inputs.config(4)
+    say("irregular workload: building both sides")
+    sim = Sim(cfg, cfg["align"], cfg["z3"], cfg["z1"], cfg["R"], cfg["sigma"], seed=0, ranks=[cfg["z3"] + 1])
+    assert len(sim.oplan["buckets"]) == 128
+    for t in (1, 2):
+        say("irregular workload step", t)
+        sim.step(t)
+        sim.compare("irregular step %d" % t)
+    oplan, plan = sim.oplan, sim.plan
+    rng = np.random.default_rng(15)
+    for bi, b in enumerate(oplan["buckets"]):
+        np_dt, t_dt = (np.uint32, torch.int32) if b["cls"] == 1 else (np.uint16, torch.int16)
+        hi = 1 << (8 * np.dtype(np_dt).itemsize)
+        bucket = rng.integers(0, hi, size=b["P"], dtype=np.uint64).astype(np_dt)
+        S3 = b["S3"]
+        shards = [np.ascontiguousarray(bucket[jj * S3:(jj + 1) * S3]) for jj in range(oplan["z3"])]
+        total = sum(oplan["tensors"][t]["numel"] for t in b["tensor_ids"])
+        pool = torch.zeros(total + 2, dtype=t_dt, device=DEV)
+        views, pos = [], 1
+        for t in b["tensor_ids"]:
+            n = oplan["tensors"][t]["numel"]
+            views.append(pool[pos:pos + n])
+            pos += n
+        full = torch.empty(b["P"], dtype=t_dt, device=DEV)
+        hzp.hzp_gather_layer(plan, b["layer"], b["cls"], 3, [to_dev(s) for s in shards], full, views)
+        torch.cuda.synchronize()
+        want = np.concatenate([on.unpack_tensor(shards, oplan["tensors"][t]["offset"], oplan["tensors"][t]["numel"])
+                               for t in b["tensor_ids"]])
+        got = to_host(pool, np_dt)
+        assert np.array_equal(got[1:1 + total], want), bi
+        assert got[0] == 0 and got[1 + total] == 0
+        assert np.array_equal(to_host(full, np_dt), on.gather_concat(shards)), bi
