@@ -35,6 +35,8 @@ def parse_args():
                     help="give every slice its own allocation instead of per-kind arenas (layout experiment)")
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
+    ap.add_argument("--secondary", default="",
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce")
     return ap.parse_args()
 
 
@@ -111,8 +113,60 @@ class Workload:
             self.l1_args.append((l, hzp.ptr_array(owners), shard3.data_ptr()))
             self.l3_args.append((l, hzp.ptr_array(shards), bucket.data_ptr()))
         self.arenas = arenas
+        self._piece, self._torch, self._hzp, self._dev = piece, torch, hzp, dev
+        self.unpack_args, self.reduce_args = None, None
         self.g_arr, self.p_arr = hzp.ptr_array(g_ptrs), hzp.ptr_array(p_ptrs)
         self.m_arr, self.v_arr, self.o_arr = hzp.ptr_array(m_ptrs), hzp.ptr_array(v_ptrs), hzp.ptr_array(o_ptrs)
+
+
+def add_secondary_buffers(w, phases):
+    """Buffers of the secondary rows (allocated only when those phases are asked for):
+    `unpack`: level-3 gather into unpadded per-tensor buffers; `reduce`: standalone fp32
+    reduction of the R bf16 contributions on the rank's ZeRO-3 gradient slice."""
+    torch, hzp, bf16 = w._torch, w._hzp, w._torch.bfloat16
+    if "unpack" in phases and w.unpack_args is None:
+        w.unpack_args, w.payload_total, tid = [], 0, 0
+        for l, b in enumerate(w.buckets):
+            recs = [w.plan.tensor(tid + t) for t in range(b.n_tensors)]
+            tid += b.n_tensors
+            total = sum(r.numel for r in recs)
+            pool = w._piece("tensors", w.p_total, bf16, b.base, total)
+            views, pos = [], 0
+            for r in recs:
+                views.append(pool[pos:pos + r.numel])
+                pos += r.numel
+            w.payload_total += total
+            w.unpack_args.append((l, w.l3_args[l][1], hzp.ptr_array(views), views))
+    if "reduce" in phases and w.reduce_args is None:
+        w.reduce_args = []
+        for l, b in enumerate(w.buckets):
+            o3 = b.base // w.cfg["z3"]
+            slices = [w._piece("rg%d" % r, w.s3_total, bf16, o3, b.s3).normal_(0.0, w.cfg["sigma"])
+                      for r in range(w.R)]
+            out = w._piece("rout", w.s3_total, torch.float32, o3, b.s3)
+            w.reduce_args.append((l, hzp.ptr_array(slices), out, slices))
+
+
+def run_secondary(w, hzp, stream, phase):
+    s = stream.cuda_stream
+    if phase == "unpack":
+        for l, shards, tensors, _ in w.unpack_args:
+            hzp.hzp_gather_layer(w.plan, l, 0, 3, shards, None, tensors, stream=s)
+    elif phase == "reduce":
+        for l, slices, out, _ in w.reduce_args:
+            hzp.hzp_reduce_shard(w.plan, l, 0, 3, w.rank, slices, w.cfg["grad_scale"], False, out, stream=s, R=w.R)
+
+
+def time_secondary(w, hzp, torch, stream, phase, steps, warmup):
+    for _ in range(warmup):
+        run_secondary(w, hzp, stream, phase)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(steps):
+        run_secondary(w, hzp, stream, phase)
+    e1.record(stream)
+    stream.synchronize()
+    return e0.elapsed_time(e1) / steps
 
 
 def run_step(w, hzp, step, stream, phases, events=None):
@@ -301,6 +355,17 @@ def main():
         "phase_ms": {"fused": round(fused_ms, 4), "gather_level1": round(g1_ms, 4),
                      "gather_level3": round(g3_ms, 4)},
     }
+    secondary = [x for x in args.secondary.split(",") if x]
+    if secondary:
+        add_secondary_buffers(w, secondary)
+        result["secondary"] = {}
+        for phase in secondary:
+            ms = time_secondary(w, hzp, torch, stream, phase, args.steps, args.warmup)
+            nbytes = 4 * w.payload_total if phase == "unpack" else (2 * R + 4) * w.s3_total
+            key = ("unpack_%s" if phase == "unpack" else "reduce_l3_%s") % cfg["name"]
+            result["secondary"][phase] = roof("unpack_kernel<2>" if phase == "unpack" else "reduce_kernel<bf16,R=%d>" % R,
+                                              nbytes, ms, w.n_layers, key)
+            result["secondary"][phase].pop("share_of_step_time")
     if not args.no_probe:
         result["hbm_probe"] = copy_probe(torch, hzp, stream)
     if not args.no_cpu_baseline:

@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 
 #include "hzp_internal.hpp"
@@ -550,20 +551,37 @@ static void launch_fused_variant(bool g32, bool o32, uint32_t R, const Seg &a, c
                                  const Wd &w, uint32_t blocks, hipStream_t stream)
 {
     const dim3 grid(blocks), block(kWave);
-    const unsigned lds = kFusedLdsBytes;
+    // The occupancy cap pays off only where every load is issued up front (compile-time R);
+    // the run-time-R loop keeps two contributions in flight and needs the resident wavefronts.
+#ifdef HZP_TUNE      // tuning builds only: sweep the occupancy cap without recompiling
+    unsigned lds = getenv("HZP_FUSED_LDS") ? (unsigned)atoi(getenv("HZP_FUSED_LDS")) : kFusedLdsBytes;
+#else
+    unsigned lds = kFusedLdsBytes;
+#endif
 #define HZP_FUSED_CASE(RT, G, O) \
-    hipLaunchKernelGGL((fused_adamw_kernel<RT, G, O, Seg, Wd>), grid, block, lds, stream, a, h, w)
+    hipLaunchKernelGGL((fused_adamw_kernel<RT, G, O, Seg, Wd>), grid, block, (RT) ? lds : 0u, stream, a, h, w)
     if (!g32 && !o32) {
         switch (R) {
+        case 1: HZP_FUSED_CASE(1, false, false); break;
+        case 2: HZP_FUSED_CASE(2, false, false); break;
         case 4: HZP_FUSED_CASE(4, false, false); break;
         case 8: HZP_FUSED_CASE(8, false, false); break;
         case 16: HZP_FUSED_CASE(16, false, false); break;
         default: HZP_FUSED_CASE(0, false, false); break;
         }
     } else if (g32 && o32) {
-        HZP_FUSED_CASE(0, true, true);
+        switch (R) {
+        case 4: HZP_FUSED_CASE(4, true, true); break;
+        case 8: HZP_FUSED_CASE(8, true, true); break;
+        case 16: HZP_FUSED_CASE(16, true, true); break;
+        default: HZP_FUSED_CASE(0, true, true); break;
+        }
     } else if (g32 && !o32) {
-        HZP_FUSED_CASE(0, true, false);
+        if (R == 1) {
+            HZP_FUSED_CASE(1, true, false);     // the pre-reduced form
+        } else {
+            HZP_FUSED_CASE(0, true, false);
+        }
     } else {
         HZP_FUSED_CASE(0, false, true);
     }
