@@ -52,9 +52,13 @@ struct DeviceTables {
     uint64_t *tensor_off = nullptr;     // [n_tensors] bucket-relative offsets, bucket after bucket
     float *tensor_wd = nullptr;         // [n_tensors] weight-decay multipliers, same order
     Piece *pieces = nullptr;            // all buckets' pieces, bucket after bucket
+    uint32_t *piece_chunk = nullptr;    // chunk_begin of the same pieces, densely packed
 };
 
-constexpr uint32_t kUnpackChunk = 4096;   // elements one wavefront moves per chunk
+#ifndef HZP_UNPACK_CHUNK
+#define HZP_UNPACK_CHUNK 1024
+#endif
+constexpr uint32_t kUnpackChunk = HZP_UNPACK_CHUNK;   // elements one wavefront moves per chunk
 
 }  // namespace hzp
 
