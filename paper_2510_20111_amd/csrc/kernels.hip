@@ -265,11 +265,13 @@ struct SegTable {
     static constexpr int kPtrCap = PTRCAP;
     uint32_t nseg;
     uint32_t R;
-    uint32_t blk_end[MAXSEG];
+    uint32_t grid2d;            // 1: grid is (groups, segments) and blk_end[s] is segment s's group count
+    uint32_t pad_;
+    uint32_t blk_end[MAXSEG];   // flat grid: running total of groups up to and including segment s
     uint32_t nquad[MAXSEG];
     const void *ptr[PTRCAP];
 };
-typedef SegTable<34, 408> SegTableWide;      // 3544 bytes: 34 layer buckets at R = 8 in one launch
+typedef SegTable<34, 408> SegTableWide;      // 3552 bytes: 34 layer buckets at R = 8 in one launch
 typedef SegTable<20, 280> SegTableNarrow;    // leaves room for the weight-decay lookup arguments
 
 struct WdLookup {
@@ -389,18 +391,29 @@ constexpr unsigned kFusedLdsBytes = 32768;
 template <int R_T, bool G32, bool O32, class Seg, class Wd>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) void fused_adamw_kernel(const Seg a, const AdamScalars h, const Wd w)
 {
-    // Which segment does this workgroup belong to?  Uniform binary search in the argument block.
-    const uint32_t blk = blockIdx.x;
-    uint32_t lo = 0, hi = a.nseg - 1;
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (blk < a.blk_end[mid])
-            hi = mid;
-        else
-            lo = mid + 1;
+    // Which segment and which group of it?  When the segments are of similar length the grid is
+    // two-dimensional (y = segment, x = group; surplus workgroups of shorter segments leave at
+    // once) and nothing is looked up; otherwise the grid is flat and a uniform binary search over
+    // the table in the argument block finds the segment.  With few wavefronts resident, the
+    // search's chain of dependent scalar loads would delay every wavefront's first memory request.
+    uint32_t seg, grp;
+    if (a.grid2d) {
+        seg = blockIdx.y;
+        grp = blockIdx.x;
+        if (grp >= a.blk_end[seg]) return;      // holds the segment's own group count in this mode
+    } else {
+        const uint32_t blk = blockIdx.x;
+        uint32_t lo = 0, hi = a.nseg - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (blk < a.blk_end[mid])
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        seg = lo;
+        grp = blk - (seg ? a.blk_end[seg - 1] : 0u);
     }
-    const uint32_t seg = lo;
-    const uint32_t grp = blk - (seg ? a.blk_end[seg - 1] : 0u);
     const uint32_t R = R_T ? (uint32_t)R_T : a.R;
     const void *const *sp = a.ptr + (size_t)seg * (R + 4);
     const uint32_t nquad = a.nquad[seg];
@@ -554,9 +567,9 @@ hzp_status_t launch_reduce(bool g32, const void *const *slices, uint32_t R, uint
 
 template <class Seg, class Wd>
 static void launch_fused_variant(bool g32, bool o32, uint32_t R, const Seg &a, const AdamScalars &h,
-                                 const Wd &w, uint32_t blocks, hipStream_t stream)
+                                 const Wd &w, dim3 grid, hipStream_t stream)
 {
-    const dim3 grid(blocks), block(kWave);
+    const dim3 block(kWave);
     // The occupancy cap pays off only where every load is issued up front (compile-time R);
     // the run-time-R loop keeps two contributions in flight and needs the resident wavefronts.
 #ifdef HZP_TUNE      // tuning builds only: sweep the occupancy cap without recompiling
@@ -635,13 +648,30 @@ static hzp_status_t launch_fused_table(const hzp_plan_t *plan, bool use_wd, bool
         if (cnt == 0) return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: shard too large for one launch");
         a.nseg = cnt;
         a.R = R;
+        // Two-dimensional grid unless the segments differ so much in length that more than an
+        // eighth of its workgroups would be surplus.
+        uint32_t max_groups = 0;
+        for (uint32_t c = 0; c < cnt; ++c) {
+            const uint32_t groups = a.blk_end[c] - (c ? a.blk_end[c - 1] : 0u);
+            max_groups = std::max(max_groups, groups);
+        }
+        dim3 grid(blocks);
+        bool two_d = (uint64_t)max_groups * cnt - blocks <= blocks / 8 && cnt <= 65535;
+#ifdef HZP_TUNE
+        if (getenv("HZP_FUSED_2D")) two_d = two_d && atoi(getenv("HZP_FUSED_2D")) != 0;
+#endif
+        if (two_d) {
+            for (uint32_t c = cnt; c-- > 0;) a.blk_end[c] -= c ? a.blk_end[c - 1] : 0u;
+            a.grid2d = 1;
+            grid = dim3(max_groups, cnt);
+        }
         if (blocks > 0) {
             if constexpr (std::is_same<Seg, SegTableNarrow>::value) {
                 w.tensor_off = tab->tensor_off;
                 w.tensor_wd = tab->tensor_wd;
-                launch_fused_variant(g32, o32, R, a, h, w, blocks, stream);
+                launch_fused_variant(g32, o32, R, a, h, w, grid, stream);
             } else {
-                launch_fused_variant(g32, o32, R, a, h, NoLookup{}, blocks, stream);
+                launch_fused_variant(g32, o32, R, a, h, NoLookup{}, grid, stream);
             }
             hzp_status_t st = check_launch("hzp_adamw_shard");
             if (st != HZP_OK) return st;
