@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
-                    help="comma list of secondary rows timed after the step loop: unpack,reduce")
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate")
     return ap.parse_args()
 
 
@@ -137,6 +137,15 @@ def add_secondary_buffers(w, phases):
                 pos += r.numel
             w.payload_total += total
             w.unpack_args.append((l, w.l3_args[l][1], hzp.ptr_array(views), views))
+    if "accumulate" in phases and getattr(w, "accum_args", None) is None:
+        # fp32 contributions accumulated into a resident fp32 gradient shard (one micro-batch)
+        w.accum_args = []
+        for l, b in enumerate(w.buckets):
+            o3 = b.base // w.cfg["z3"]
+            slices = [w._piece("ag%d" % r, w.s3_total, torch.float32, o3, b.s3).normal_(0.0, w.cfg["sigma"])
+                      for r in range(w.R)]
+            acc = w._piece("acc", w.s3_total, torch.float32, o3, b.s3).zero_()
+            w.accum_args.append((l, hzp.ptr_array(slices), acc, slices))
     if "reduce" in phases and w.reduce_args is None:
         w.reduce_args = []
         for l, b in enumerate(w.buckets):
@@ -152,6 +161,10 @@ def run_secondary(w, hzp, stream, phase):
     if phase == "unpack":
         for l, shards, tensors, _ in w.unpack_args:
             hzp.hzp_gather_layer(w.plan, l, 0, 3, shards, None, tensors, stream=s)
+    elif phase == "accumulate":
+        for l, slices, acc, _ in w.accum_args:
+            hzp.hzp_reduce_shard(w.plan, l, 0, 3, w.rank, slices, w.cfg["grad_scale"], True, acc, stream=s, R=w.R,
+                                 grad_dtype=hzp.HZP_GRAD_F32)
     elif phase == "reduce":
         for l, slices, out, _ in w.reduce_args:
             hzp.hzp_reduce_shard(w.plan, l, 0, 3, w.rank, slices, w.cfg["grad_scale"], False, out, stream=s, R=w.R)
@@ -361,10 +374,11 @@ def main():
         result["secondary"] = {}
         for phase in secondary:
             ms = time_secondary(w, hzp, torch, stream, phase, args.steps, args.warmup)
-            nbytes = 4 * w.payload_total if phase == "unpack" else (2 * R + 4) * w.s3_total
-            key = ("unpack_%s" if phase == "unpack" else "reduce_l3_%s") % cfg["name"]
-            result["secondary"][phase] = roof("unpack_kernel<2>" if phase == "unpack" else "reduce_kernel<bf16,R=%d>" % R,
-                                              nbytes, ms, w.n_layers, key)
+            nbytes = {"unpack": lambda: 4 * w.payload_total, "reduce": lambda: (2 * R + 4) * w.s3_total,
+                      "accumulate": lambda: (4 * R + 8) * w.s3_total}[phase]()
+            kname = {"unpack": "unpack_kernel<2>", "reduce": "reduce_kernel<bf16,R=%d>" % R,
+                     "accumulate": "reduce_kernel<f32,R=%d,accumulate>" % R}[phase]
+            result["secondary"][phase] = roof(kname, nbytes, ms, w.n_layers, "%s_%s" % (phase, cfg["name"]))
             result["secondary"][phase].pop("share_of_step_time")
     if not args.no_probe:
         result["hbm_probe"] = copy_probe(torch, hzp, stream)

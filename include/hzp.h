@@ -53,6 +53,11 @@ typedef enum {
  * out (1-D norm / bias states that are kept in full precision). */
 typedef enum { HZP_CLASS_BF16 = 0, HZP_CLASS_F32 = 1 } hzp_class_t;
 
+/* Element type of gradient contributions handed to hzp_reduce_shard.  DEFAULT: the class's own
+ * (bf16 for BF16 buckets, fp32 for F32 buckets).  F32 on a BF16 bucket is the paper's literal
+ * setting: fp32 gradients (Table 1) next to bf16 parameters. */
+typedef enum { HZP_GRAD_DEFAULT = 0, HZP_GRAD_BF16 = 1, HZP_GRAD_F32 = 2 } hzp_grad_dtype_t;
+
 #define HZP_MAX_REPLICAS 32u    /* largest R accepted by the reduce / update entry points */
 #define HZP_MAX_GROUP    64u    /* largest number of shards one gather call concatenates */
 
@@ -140,6 +145,13 @@ hzp_status_t hzp_plan_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls
 hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt_bytes, uint64_t *grad_bytes,
                             uint64_t *param_bytes);
 
+/* Static model-state memory per device of Section 4.1.1 for N parameters,
+ *     M_hzp = 12N/Z1 + 4N/Z2 + 2N/Z3   bytes,
+ * evaluated exactly and rounded up to a whole byte.  Z1 = Z2 = Z3 = Z gives M_zp = 18N/Z, and
+ * Z = DP gives vanilla ZeRO-3, M_zero3 = 18N/DP.  Host-only.
+ * Errors: INVALID_ARG (NULL output, a group size of 0), UNSUPPORTED (result exceeds 64 bits). */
+hzp_status_t hzp_memory_model(uint64_t n_params, uint32_t z1, uint32_t z2, uint32_t z3, uint64_t *bytes);
+
 /* ------------------------------------------------------------------------------------------
  * Gradient reduction on the rank's shard: the arithmetic half of the per-layer reduce-scatter
  * ("performed using the float32 data type", Section 4.1.2, Backward Pass) together with the
@@ -151,16 +163,18 @@ hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt_bytes, uint64_
  * for x in [0, n), n = S1 (level 1) or S3 (level 3) of bucket (layer, cls).  The result equals
  * the scalar definition bit for bit.
  *   grad_slices : host array [R] of device pointers; entry r points at element 0 of the rank's
- *                 slice inside contribution r (bf16 for class BF16, fp32 for class F32), n
- *                 elements, 16-byte aligned
+ *                 slice inside contribution r, n elements of `grad_dtype`, 16-byte aligned
  *   R           : 1 .. HZP_MAX_REPLICAS
+ *   grad_dtype  : an hzp_grad_dtype_t
+ *   accumulate  : non-zero adds the scaled sum to what `out_f32` holds: the per-micro-batch
+ *                 accumulation of Section 4.2 ("aggregate gradients of every micro batch")
  *   out_f32     : device pointer, n floats, 16-byte aligned; read first when accumulate != 0;
  *                 must not overlap any input
  * Errors: INVALID_ARG, RANGE (layer / class / level / rank), UNSUPPORTED (R too large, or a shard of 2^30 elements or more), ALIGN, HIP.
  * ------------------------------------------------------------------------------------------ */
 hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level, uint32_t rank,
-                              const void *const *grad_slices, uint32_t R, float scale, int accumulate,
-                              float *out_f32, hipStream_t stream);
+                              const void *const *grad_slices, uint32_t R, uint32_t grad_dtype, float scale,
+                              int accumulate, float *out_f32, hipStream_t stream);
 
 /* ------------------------------------------------------------------------------------------
  * Fused shard update: reduction as above (scale = grad_scale, no accumulate), then Adam with

@@ -4,9 +4,10 @@ The product is ``libhzp.so`` (HIP kernels for gfx950 behind the C ABI of ``inclu
 this package is its thin ctypes binding.  Importing it requires the built library.
 """
 from .binding import (  # noqa: F401
-    HZP_CLASS_BF16, HZP_CLASS_F32, HZP_MAX_GROUP, HZP_MAX_REPLICAS,
+    HZP_CLASS_BF16, HZP_CLASS_F32, HZP_GRAD_DEFAULT, HZP_GRAD_BF16, HZP_GRAD_F32, HZP_MAX_GROUP,
+    HZP_MAX_REPLICAS,
     HZP_OK, HZP_ERR_INVALID_ARG, HZP_ERR_RANGE, HZP_ERR_UNSUPPORTED, HZP_ERR_ALIGN,
     HZP_ERR_NOMEM, HZP_ERR_HIP,
     EXPORTS, LIB_PATH, HzpError, Plan, adamw_hyper, ptr_array,
-    hzp_plan, hzp_plan_free, hzp_reduce_shard, hzp_adamw_shard, hzp_gather_layer, hzp_last_error,
+    hzp_plan, hzp_plan_free, hzp_memory_model, hzp_reduce_shard, hzp_adamw_shard, hzp_gather_layer, hzp_last_error,
 )

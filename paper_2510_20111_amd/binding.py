@@ -14,13 +14,14 @@ LIB_PATH = os.path.join(_HERE, "libhzp.so")
 HZP_OK, HZP_ERR_INVALID_ARG, HZP_ERR_RANGE, HZP_ERR_UNSUPPORTED, HZP_ERR_ALIGN, HZP_ERR_NOMEM, \
     HZP_ERR_HIP = range(7)
 HZP_CLASS_BF16, HZP_CLASS_F32 = 0, 1
+HZP_GRAD_DEFAULT, HZP_GRAD_BF16, HZP_GRAD_F32 = 0, 1, 2
 HZP_MAX_REPLICAS, HZP_MAX_GROUP = 32, 64
 _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSUPPORTED",
                  "HZP_ERR_ALIGN", "HZP_ERR_NOMEM", "HZP_ERR_HIP"]
 
 EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
            "hzp_plan_rank", "hzp_plan_shard", "hzp_plan_bytes", "hzp_reduce_shard",
-           "hzp_adamw_shard", "hzp_gather_layer", "hzp_last_error"]
+           "hzp_adamw_shard", "hzp_gather_layer", "hzp_last_error", "hzp_memory_model"]
 
 
 class HzpError(RuntimeError):
@@ -94,13 +95,15 @@ def _load():
     L.hzp_plan_bytes.restype = ctypes.c_int
     L.hzp_plan_bytes.argtypes = [vp, u64p, u64p, u64p]
     L.hzp_reduce_shard.restype = ctypes.c_int
-    L.hzp_reduce_shard.argtypes = [vp, u32, u32, ctypes.c_int, u32, vp, u32, ctypes.c_float,
+    L.hzp_reduce_shard.argtypes = [vp, u32, u32, ctypes.c_int, u32, vp, u32, u32, ctypes.c_float,
                                    ctypes.c_int, vp, vp]
     L.hzp_adamw_shard.restype = ctypes.c_int
     L.hzp_adamw_shard.argtypes = [vp, u32, u32, u32, u32, ctypes.POINTER(AdamW), vp, u32,
                                   vp, vp, vp, vp, vp]
     L.hzp_gather_layer.restype = ctypes.c_int
     L.hzp_gather_layer.argtypes = [vp, u32, u32, ctypes.c_int, vp, u32, vp, vp, vp]
+    L.hzp_memory_model.restype = ctypes.c_int
+    L.hzp_memory_model.argtypes = [ctypes.c_uint64, u32, u32, u32, u64p]
     L.hzp_last_error.restype = ctypes.c_char_p
     L.hzp_last_error.argtypes = []
     return L
@@ -203,15 +206,21 @@ def hzp_plan(tensors_per_layer, tensor_numel, align, z3, z1, z2=0, tensor_class=
     return Plan(handle, None)
 
 
+def hzp_memory_model(n_params, z1, z2, z3):
+    out = ctypes.c_uint64()
+    _check(_L.hzp_memory_model(n_params, z1, z2, z3, ctypes.byref(out)))
+    return out.value
+
+
 def hzp_plan_free(plan):
     plan.__del__()
 
 
 def hzp_reduce_shard(plan, layer, cls, level, rank, grad_slices, scale, accumulate, out_f32,
-                     stream=None, R=None):
+                     stream=None, R=None, grad_dtype=HZP_GRAD_DEFAULT):
     arr = ptr_array(grad_slices)
     _check(_L.hzp_reduce_shard(plan.handle, layer, cls, level, rank, arr,
-                               len(arr) if R is None else R, scale, int(bool(accumulate)),
+                               len(arr) if R is None else R, grad_dtype, scale, int(bool(accumulate)),
                                _addr(out_f32), _stream(stream)))
 
 

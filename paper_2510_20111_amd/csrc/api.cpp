@@ -17,7 +17,8 @@ using namespace hzp;
 
 extern "C" hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level,
                                          uint32_t rank, const void *const *grad_slices, uint32_t R,
-                                         float scale, int accumulate, float *out_f32, hipStream_t stream)
+                                         uint32_t grad_dtype, float scale, int accumulate, float *out_f32,
+                                         hipStream_t stream)
 {
     if (!plan || !grad_slices || !out_f32)
         return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: NULL plan, slice array or output");
@@ -26,6 +27,8 @@ extern "C" hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer,
     if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_reduce_shard: rank %u of %u", rank, plan->z1);
     if (level != 1 && level != 3)
         return fail(HZP_ERR_RANGE, "hzp_reduce_shard: level %d is neither 1 nor 3", level);
+    if (grad_dtype > HZP_GRAD_F32)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: unknown gradient type %u", grad_dtype);
     if (R == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: R must be at least 1");
     if (R > HZP_MAX_REPLICAS)
         return fail(HZP_ERR_UNSUPPORTED, "hzp_reduce_shard: R=%u exceeds %u", R, HZP_MAX_REPLICAS);
@@ -37,7 +40,8 @@ extern "C" hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer,
             return fail(HZP_ERR_ALIGN, "hzp_reduce_shard: slice %u is not 16-byte aligned", r);
     }
     if (!aligned16(out_f32)) return fail(HZP_ERR_ALIGN, "hzp_reduce_shard: output is not 16-byte aligned");
-    return launch_reduce(cls == HZP_CLASS_F32, grad_slices, R, n, scale, accumulate, out_f32, stream);
+    const bool g32 = grad_dtype == HZP_GRAD_DEFAULT ? cls == HZP_CLASS_F32 : grad_dtype == HZP_GRAD_F32;
+    return launch_reduce(g32, grad_slices, R, n, scale, accumulate, out_f32, stream);
 }
 
 extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,

@@ -284,3 +284,27 @@ extern "C" hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt, ui
     if (par) *par = q;
     return HZP_OK;
 }
+
+extern "C" hzp_status_t hzp_memory_model(uint64_t n, uint32_t z1, uint32_t z2, uint32_t z3, uint64_t *bytes)
+{
+    if (!bytes) return fail(HZP_ERR_INVALID_ARG, "hzp_memory_model: NULL output");
+    if (z1 == 0 || z2 == 0 || z3 == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_memory_model: group size 0");
+    // (12 n z2 z3 + 4 n z1 z3 + 2 n z1 z2) / (z1 z2 z3), exactly, in 128-bit integers:
+    // n < 2^64 and each group size < 2^32 keep the numerator below 2^(64+4+64) only if
+    // checked, so every product is tested for overflow.
+    typedef unsigned __int128 u128;
+    const u128 a = (u128)z2 * z3, b = (u128)z1 * z3, c = (u128)z1 * z2;    // each < 2^64
+    const u128 den = a * z1;                                               // < 2^96
+    u128 num = 0;
+    const u128 terms[3] = {12 * a, 4 * b, 2 * c};                          // each < 2^68
+    for (const u128 t : terms) {
+        if (n != 0 && t > (~(u128)0) / n) return fail(HZP_ERR_UNSUPPORTED, "hzp_memory_model: overflow");
+        const u128 add = t * n;
+        if (num + add < num) return fail(HZP_ERR_UNSUPPORTED, "hzp_memory_model: overflow");
+        num += add;
+    }
+    const u128 q = num / den + (num % den != 0);
+    if (q >> 64) return fail(HZP_ERR_UNSUPPORTED, "hzp_memory_model: result exceeds 64 bits");
+    *bytes = (uint64_t)q;
+    return HZP_OK;
+}

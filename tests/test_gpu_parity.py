@@ -446,3 +446,69 @@ def test_unpack_more_tensors_than_one_launch_carries():
     want = np.concatenate([on.unpack_tensor(shards, oplan["tensors"][t]["offset"], numel[t]) for t in range(1000)])
     got = to_host(pool, np.uint16)
     assert np.array_equal(got[1:1 + want.size], want) and got[0] == 0 and not got[1 + want.size:].any()
+
+
+# ------------------------------------------------------------------------------ next rows
+
+def test_gradient_accumulation_with_fp32_gradients_then_prereduced_update():
+    """The paper's literal setting: fp32 gradients (Table 1), one reduce-scatter per micro-batch
+    accumulated into a resident fp32 gradient shard (Section 4.2), then the optimizer step from that
+    shard (R == 0 form).  Accumulator bit-exact after every micro-batch; update within tolerance."""
+    say("accumulation flow")
+    desc = dict(tensors_per_layer=[2, 1], tensor_numel=[7001, 1300, 2048 * 5 + 24])
+    oplan, plan = oracle_plan(desc, 8, 2, 4), lib_plan(desc, 8, 2, 4)
+    R, M, rank = 4, 3, 3
+    rng = np.random.default_rng(16)
+    hy = hzp.adamw_hyper(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], 1.0 / M, 1)
+    host, dev = [], []
+    for layer, b in enumerate(oplan["buckets"]):
+        _, n = op.shard_range(oplan, b, 1, rank)
+        h = dict(acc=np.zeros(n, np.float32), p=(rng.standard_normal(n) * 0.02).astype(np.float32),
+                 m=(rng.standard_normal(n) * 1e-4).astype(np.float32), v=(rng.random(n) * 1e-7).astype(np.float32))
+        host.append(h)
+        dev.append(dict(acc=torch.full((n,), 7.0, device=DEV), p=to_dev(h["p"]), m=to_dev(h["m"]), v=to_dev(h["v"]),
+                        out=torch.empty(n, dtype=torch.int16, device=DEV)))
+    for mb in range(M):
+        for layer, b in enumerate(oplan["buckets"]):
+            n = host[layer]["acc"].size
+            g = [(rng.standard_normal(n) * 1e-3).astype(np.float32) for _ in range(R)]
+            on.reduce(g, scale=1.0 / R, accumulate=(mb > 0), out=host[layer]["acc"])
+            hzp.hzp_reduce_shard(plan, layer, 0, 1, rank, [to_dev(x) for x in g], 1.0 / R, mb > 0,
+                                 dev[layer]["acc"], grad_dtype=hzp.HZP_GRAD_F32)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_host(dev[layer]["acc"], np.uint32), host[layer]["acc"].view(np.uint32)), (mb, layer)
+    hzp.hzp_adamw_shard(plan, 0, 2, 0, rank, hy, [d["acc"] for d in dev], 0, [d["p"] for d in dev],
+                        [d["m"] for d in dev], [d["v"] for d in dev], [d["out"] for d in dev])
+    torch.cuda.synchronize()
+    for layer, (h, d) in enumerate(zip(host, dev)):
+        g = on.reduce([h["acc"]], scale=1.0 / M)
+        want16 = on.adamw(g, h["p"], h["m"], h["v"], step=1, **HP)
+        for key in ("p", "m", "v"):
+            assert_close_f32(to_host(d[key], np.float32), h[key], "layer %d %s" % (layer, key))
+        assert_bf16_within_one_ulp(to_host(d["out"], np.uint16), want16, "layer %d bf16" % layer, h["p"])
+
+
+def test_update_can_write_straight_into_the_zero3_shard():
+    """param_out may point at the rank's piece k*S1 of the ZeRO-3 parameter shard buffer, which
+    makes the local part of the post-step gather (Section 4.1.2, Optimizer Step) disappear."""
+    say("update into the ZeRO-3 shard")
+    desc = dict(tensors_per_layer=[1], tensor_numel=[8 * 4 * 700])
+    oplan, plan = oracle_plan(desc, 8, 2, 8), lib_plan(desc, 8, 2, 8)
+    b = oplan["buckets"][0]
+    rank, R = 5, 2                       # j = 1, k = 2
+    j, k, i = op.rank_to_indices(oplan, rank)
+    S1, S3 = b["S1"], b["S3"]
+    rng = np.random.default_rng(17)
+    g = [hzp_inputs.to_bf16_bits((rng.standard_normal(S1) * 1e-3).astype(np.float32)) for _ in range(R)]
+    p0 = (rng.standard_normal(S1) * 0.02).astype(np.float32)
+    shard3 = torch.full((S3,), 0x7FC1, dtype=torch.int16, device=DEV)
+    p, m, v = to_dev(p0), torch.zeros(S1, device=DEV), torch.zeros(S1, device=DEV)
+    hy = hzp.adamw_hyper(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], 0.5, 1)
+    hzp.hzp_adamw_shard(plan, 0, 1, 0, rank, hy, [to_dev(x) for x in g], R, [p], [m], [v],
+                        [shard3[k * S1:(k + 1) * S1]])
+    torch.cuda.synchronize()
+    po, mo, vo = p0.copy(), np.zeros(S1, np.float32), np.zeros(S1, np.float32)
+    want16 = on.adamw(on.reduce(g, scale=0.5), po, mo, vo, step=1, **HP)
+    got = to_host(shard3, np.uint16)
+    assert_bf16_within_one_ulp(got[k * S1:(k + 1) * S1], want16, "piece in the shard", po)
+    assert (got[:k * S1] == 0x7FC1).all() and (got[(k + 1) * S1:] == 0x7FC1).all()

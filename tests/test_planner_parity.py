@@ -75,3 +75,28 @@ def test_paper_group_sizes():
     for z1 in (64, 256):
         _compare(dict(c, z1=z1, tensors_per_layer=c["tensors_per_layer"][:3],
                       tensor_numel=c["tensor_numel"][:27]))
+
+
+def test_memory_model_matches_closed_form():
+    """hzp_memory_model against the oracle's exact fraction and the hand-worked golden values."""
+    import math
+    import os
+    from fractions import Fraction
+    golden = os.path.join(os.path.dirname(__file__), "golden", "memory_model.txt")
+    for line in open(golden):
+        line = line.split("#")[0].split()
+        if line:
+            N, z1, z2, z3, want = (int(x) for x in line)
+            assert hzp.hzp_memory_model(N, z1, z2, z3) == want
+    for N, z1, z2, z3 in [(7, 3, 5, 2), (10 ** 12 + 1, 64, 8, 8), (1, 1, 1, 1), (0, 4, 4, 4),
+                          (2 ** 60, 2 ** 31, 3, 7), (123456789, 256, 8, 8)]:
+        assert hzp.hzp_memory_model(N, z1, z2, z3) == math.ceil(op.hzp_memory_bytes(N, z1, z2, z3))
+    # the plan's per-rank bytes are the same model with N -> padded length
+    c = hzp_inputs.config(1)
+    plan = hzp.hzp_plan(c["tensors_per_layer"], c["tensor_numel"], c["align"], c["z3"], c["z1"])
+    assert sum(plan.bytes()) == hzp.hzp_memory_model(plan.info().total_padded, c["z1"], c["z3"], c["z3"])
+    import pytest
+    with pytest.raises(hzp.HzpError):
+        hzp.hzp_memory_model(5, 0, 1, 1)
+    with pytest.raises(hzp.HzpError):
+        hzp.hzp_memory_model(2 ** 63, 1, 1, 1)
