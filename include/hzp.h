@@ -235,6 +235,64 @@ hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer, uint32_t c
                               const void *const *shard_ptrs, uint32_t n_shards, void *bucket_out,
                               void *const *tensor_out, hipStream_t stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Asynchronous scheduler: the multi-stream dispatch of Section 4.2 for the local halves of the
+ * collectives.  A scheduler owns one background host thread, two dedicated streams (gathers,
+ * reductions; default priority) and a fixed-capacity persistent pool of `gather_slots` contiguous
+ * layer-bucket buffers that are reused cyclically.  Issuing a prefetch or a reduction returns at
+ * once and puts nothing on the caller's compute stream; the compute stream waits for a layer's
+ * parameters only where it acquires them, and a slot is given back right after its use.
+ *
+ * Protocol per layer: prefetch -> acquire -> (use on `consumer`) -> release.  Layers must be
+ * released in the order they were prefetched (the pool is a cycle), and at most `gather_slots`
+ * layers can be between prefetch and release: one more prefetch returns HZP_ERR_NOMEM (back
+ * pressure) instead of blocking.  Host-side waits inside these calls are bounded (30 s) and then
+ * fail with HZP_ERR_HIP; after any failure every later call on the scheduler returns that status.
+ * All calls may come from one thread at a time; the plan must outlive the scheduler.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct hzp_sched hzp_sched_t;
+
+typedef struct {
+    uint32_t cls;               /* class of the buckets this scheduler gathers and reduces */
+    uint32_t gather_slots;      /* pool capacity in layer buckets = how far prefetch can run ahead, >= 1 */
+    uint32_t queue_capacity;    /* commands that may wait for the background thread, >= 1 */
+} hzp_sched_desc_t;
+
+typedef struct {
+    uint64_t pool_bytes;            /* size of the persistent pool (allocated once) */
+    uint64_t slot_bytes;            /* size of one slot: the largest bucket, rounded to 256 bytes */
+    uint64_t peak_live_bytes;       /* most bucket bytes that were between prefetch and release at once */
+    uint32_t peak_live_slots;
+    uint32_t reserved_;
+    uint64_t gathers_issued, reduces_issued;
+    uint64_t acquire_host_wait_us;  /* host time spent in acquire waiting for the gather to be issued */
+} hzp_sched_stats_t;
+
+/* Allocates the pool on the current device and starts the thread.  Errors: INVALID_ARG, RANGE
+ * (no bucket of that class), NOMEM, HIP. */
+hzp_status_t hzp_sched_create(const hzp_plan_t *plan, const hzp_sched_desc_t *desc, hzp_sched_t **out);
+/* Launches what is still queued, waits for the side streams, frees everything.  NULL allowed. */
+void hzp_sched_destroy(hzp_sched_t *sched);
+/* Queue the level-3 gather of `layer` (hzp_gather_layer with bucket_out = the next pool slot).
+ * shard_ptrs: host array [Z3] of device pointers, copied.  Returns at once. */
+hzp_status_t hzp_sched_prefetch(hzp_sched_t *sched, uint32_t layer, const void *const *shard_ptrs, uint32_t n_shards);
+/* Make `consumer` wait for the layer's gather and return the bucket's device address.  Blocks the
+ * host only until the background thread has launched that gather. */
+hzp_status_t hzp_sched_acquire(hzp_sched_t *sched, uint32_t layer, hipStream_t consumer, void **bucket);
+/* The work enqueued on `consumer` so far is the last use of the layer's bucket. */
+hzp_status_t hzp_sched_release(hzp_sched_t *sched, uint32_t layer, hipStream_t consumer);
+/* Queue hzp_reduce_shard(layer, level, rank, ...) on the reduction stream, to run after the work
+ * already enqueued on `producer` (which wrote the gradients).  Pointer array copied.  Returns at once. */
+hzp_status_t hzp_sched_reduce(hzp_sched_t *sched, uint32_t layer, int level, uint32_t rank,
+                              const void *const *grad_slices, uint32_t R, uint32_t grad_dtype, float scale,
+                              int accumulate, float *out_f32, hipStream_t producer);
+/* Make `consumer` wait for everything queued before this call (both side streams).  Blocks the
+ * host until those commands have been launched. */
+hzp_status_t hzp_sched_join(hzp_sched_t *sched, hipStream_t consumer);
+/* Block the host until everything queued so far has been launched and has finished. */
+hzp_status_t hzp_sched_drain(hzp_sched_t *sched);
+hzp_status_t hzp_sched_stats(hzp_sched_t *sched, hzp_sched_stats_t *out);
+
 /* Text of the calling thread's last non-OK status ("" if none).  Valid until that thread's next
  * failing call. */
 const char *hzp_last_error(void);

@@ -21,7 +21,9 @@ _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSU
 
 EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
            "hzp_plan_rank", "hzp_plan_shard", "hzp_plan_bytes", "hzp_reduce_shard",
-           "hzp_adamw_shard", "hzp_gather_layer", "hzp_last_error", "hzp_memory_model"]
+           "hzp_adamw_shard", "hzp_gather_layer", "hzp_last_error", "hzp_memory_model",
+           "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_acquire",
+           "hzp_sched_release", "hzp_sched_reduce", "hzp_sched_join", "hzp_sched_drain", "hzp_sched_stats"]
 
 
 class HzpError(RuntimeError):
@@ -59,6 +61,18 @@ class TensorInfo(ctypes.Structure):
                 ("bucket_index", ctypes.c_uint32), ("index_in_bucket", ctypes.c_uint32),
                 ("offset", ctypes.c_uint64), ("numel", ctypes.c_uint64),
                 ("wd_mult", ctypes.c_float)]
+
+
+class SchedDesc(ctypes.Structure):
+    _fields_ = [("cls", ctypes.c_uint32), ("gather_slots", ctypes.c_uint32),
+                ("queue_capacity", ctypes.c_uint32)]
+
+
+class SchedStats(ctypes.Structure):
+    _fields_ = [("pool_bytes", ctypes.c_uint64), ("slot_bytes", ctypes.c_uint64),
+                ("peak_live_bytes", ctypes.c_uint64), ("peak_live_slots", ctypes.c_uint32),
+                ("reserved_", ctypes.c_uint32), ("gathers_issued", ctypes.c_uint64),
+                ("reduces_issued", ctypes.c_uint64), ("acquire_host_wait_us", ctypes.c_uint64)]
 
 
 class AdamW(ctypes.Structure):
@@ -104,6 +118,24 @@ def _load():
     L.hzp_gather_layer.argtypes = [vp, u32, u32, ctypes.c_int, vp, u32, vp, vp, vp]
     L.hzp_memory_model.restype = ctypes.c_int
     L.hzp_memory_model.argtypes = [ctypes.c_uint64, u32, u32, u32, u64p]
+    L.hzp_sched_create.restype = ctypes.c_int
+    L.hzp_sched_create.argtypes = [vp, ctypes.POINTER(SchedDesc), ctypes.POINTER(vp)]
+    L.hzp_sched_destroy.restype = None
+    L.hzp_sched_destroy.argtypes = [vp]
+    L.hzp_sched_prefetch.restype = ctypes.c_int
+    L.hzp_sched_prefetch.argtypes = [vp, u32, vp, u32]
+    L.hzp_sched_acquire.restype = ctypes.c_int
+    L.hzp_sched_acquire.argtypes = [vp, u32, vp, ctypes.POINTER(vp)]
+    L.hzp_sched_release.restype = ctypes.c_int
+    L.hzp_sched_release.argtypes = [vp, u32, vp]
+    L.hzp_sched_reduce.restype = ctypes.c_int
+    L.hzp_sched_reduce.argtypes = [vp, u32, ctypes.c_int, u32, vp, u32, u32, ctypes.c_float, ctypes.c_int, vp, vp]
+    L.hzp_sched_join.restype = ctypes.c_int
+    L.hzp_sched_join.argtypes = [vp, vp]
+    L.hzp_sched_drain.restype = ctypes.c_int
+    L.hzp_sched_drain.argtypes = [vp]
+    L.hzp_sched_stats.restype = ctypes.c_int
+    L.hzp_sched_stats.argtypes = [vp, ctypes.POINTER(SchedStats)]
     L.hzp_last_error.restype = ctypes.c_char_p
     L.hzp_last_error.argtypes = []
     return L
@@ -244,3 +276,49 @@ def hzp_gather_layer(plan, layer, cls, level, shard_ptrs, bucket_out=None, tenso
                                len(arr) if n_shards is None else n_shards, _addr(bucket_out),
                                ptr_array(tensor_out) if tensor_out is not None else None,
                                _stream(stream)))
+
+
+class Sched:
+    """Owner of an ``hzp_sched_t*`` (hzp_sched_create ... hzp_sched_destroy)."""
+
+    def __init__(self, plan, cls=HZP_CLASS_BF16, gather_slots=2, queue_capacity=64):
+        self.plan = plan                      # keeps the plan alive
+        desc = SchedDesc(cls, gather_slots, queue_capacity)
+        self.handle = ctypes.c_void_p()
+        _check(_L.hzp_sched_create(plan.handle, ctypes.byref(desc), ctypes.byref(self.handle)))
+
+    def destroy(self):
+        if getattr(self, "handle", None):
+            _L.hzp_sched_destroy(self.handle)
+            self.handle = None
+
+    __del__ = destroy
+
+    def prefetch(self, layer, shard_ptrs):
+        arr = ptr_array(shard_ptrs)
+        _check(_L.hzp_sched_prefetch(self.handle, layer, arr, len(arr)))
+
+    def acquire(self, layer, consumer=None):
+        out = ctypes.c_void_p()
+        _check(_L.hzp_sched_acquire(self.handle, layer, _stream(consumer), ctypes.byref(out)))
+        return out.value
+
+    def release(self, layer, consumer=None):
+        _check(_L.hzp_sched_release(self.handle, layer, _stream(consumer)))
+
+    def reduce(self, layer, level, rank, grad_slices, scale, accumulate, out_f32, producer=None,
+               grad_dtype=HZP_GRAD_DEFAULT):
+        arr = ptr_array(grad_slices)
+        _check(_L.hzp_sched_reduce(self.handle, layer, level, rank, arr, len(arr), grad_dtype, scale,
+                                   int(bool(accumulate)), _addr(out_f32), _stream(producer)))
+
+    def join(self, consumer=None):
+        _check(_L.hzp_sched_join(self.handle, _stream(consumer)))
+
+    def drain(self):
+        _check(_L.hzp_sched_drain(self.handle))
+
+    def stats(self):
+        out = SchedStats()
+        _check(_L.hzp_sched_stats(self.handle, ctypes.byref(out)))
+        return out

@@ -4,7 +4,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["planner.cpp", "api.cpp", "kernels.hip"]
+SOURCES = ["planner.cpp", "api.cpp", "scheduler.cpp", "kernels.hip"]
 LIB = os.path.join(HERE, "libhzp.so")
 
 
@@ -13,7 +13,7 @@ def build(verbose=False):
     cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            # packed fp32 instructions stay off (see the hipcc flag of the same name)
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-command-line-argument",
+           "-Wall", "-Wno-unused-command-line-argument", "-pthread",
            "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
     cmd += [os.path.join(HERE, "csrc", s) for s in SOURCES]
     cmd += ["-o", LIB]

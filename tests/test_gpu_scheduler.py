@@ -1,0 +1,156 @@
+"""The asynchronous scheduler (background thread, dedicated streams, cyclic persistent pool):
+results must equal the synchronous entry points' and the oracle's, bit for bit, whatever the
+interleaving with a busy compute stream."""
+import numpy as np
+import pytest
+import torch
+
+import hzp_inputs
+import paper_2510_20111_amd as hzp
+from oracle import numeric as on
+from oracle import planner as op
+
+from gpu_util import DEV, oracle_plan, to_dev, to_host
+from test_gpu_parity import lib_plan, say
+
+pytestmark = pytest.mark.gpu
+
+
+class _DevView:
+    """Zero-copy torch view of `n` int16 elements at a raw device address."""
+
+    def __init__(self, ptr, n):
+        self.__cuda_array_interface__ = {"shape": (n,), "typestr": "<i2", "data": (ptr, False), "version": 3}
+
+
+def view16(ptr, n):
+    return torch.as_tensor(_DevView(ptr, n), device=DEV)
+
+
+def _layers(n_layers, seed):
+    rng = np.random.default_rng(seed)
+    numel = [int(x) for x in rng.integers(20000, 90000, size=n_layers)]
+    desc = dict(tensors_per_layer=[1] * n_layers, tensor_numel=numel)
+    oplan, plan = oracle_plan(desc, 8, 4, 8), lib_plan(desc, 8, 4, 8)
+    shards = []
+    for b in oplan["buckets"]:
+        bucket = rng.integers(0, 1 << 16, size=b["P"], dtype=np.uint64).astype(np.uint16)
+        shards.append([np.ascontiguousarray(bucket[j * b["S3"]:(j + 1) * b["S3"]]) for j in range(4)])
+    return oplan, plan, shards
+
+
+def test_prefetch_pipeline_through_a_two_slot_pool():
+    say("scheduler: prefetch pipeline")
+    n_layers = 9
+    oplan, plan, shards = _layers(n_layers, 50)
+    dshards = [[to_dev(s) for s in layer] for layer in shards]
+    sched = hzp.Sched(plan, gather_slots=2, queue_capacity=4)
+    consumer = torch.cuda.Stream()
+    busy = torch.randn(2048, 2048, device=DEV)
+    outs = [torch.zeros(oplan["buckets"][l]["P"], dtype=torch.int16, device=DEV) for l in range(n_layers)]
+    torch.cuda.synchronize()
+    sched.prefetch(0, dshards[0])
+    sched.prefetch(1, dshards[1])
+    for l in range(n_layers):
+        with torch.cuda.stream(consumer):
+            busy = busy @ busy * 1e-3                 # keeps the compute stream behind the gathers
+        ptr = sched.acquire(l, consumer)
+        with torch.cuda.stream(consumer):
+            outs[l].copy_(view16(ptr, outs[l].numel()))
+        sched.release(l, consumer)
+        if l + 2 < n_layers:
+            sched.prefetch(l + 2, dshards[l + 2])
+    consumer.synchronize()
+    sched.drain()
+    for l in range(n_layers):
+        want = on.gather_concat(shards[l])
+        assert np.array_equal(to_host(outs[l], np.uint16), want), l
+    st = sched.stats()
+    assert st.gathers_issued == n_layers and st.peak_live_slots == 2
+    assert st.pool_bytes == 2 * st.slot_bytes
+    assert st.slot_bytes >= 2 * max(b["P"] for b in oplan["buckets"])
+    assert st.peak_live_bytes <= st.pool_bytes
+    sched.destroy()
+
+
+def test_protocol_errors_and_back_pressure():
+    say("scheduler: protocol errors")
+    oplan, plan, shards = _layers(4, 51)
+    dshards = [[to_dev(s) for s in layer] for layer in shards]
+    sched = hzp.Sched(plan, gather_slots=2, queue_capacity=8)
+
+    def status(fn, *a):
+        with pytest.raises(hzp.HzpError) as e:
+            fn(*a)
+        return e.value.status
+
+    assert status(sched.acquire, 0) == hzp.HZP_ERR_INVALID_ARG          # never prefetched
+    assert status(sched.prefetch, 9, dshards[0]) == hzp.HZP_ERR_RANGE
+    assert status(sched.prefetch, 0, dshards[0][:3]) == hzp.HZP_ERR_INVALID_ARG
+    sched.prefetch(0, dshards[0])
+    assert status(sched.prefetch, 0, dshards[0]) == hzp.HZP_ERR_INVALID_ARG   # already in the pool
+    sched.prefetch(1, dshards[1])
+    assert status(sched.prefetch, 2, dshards[2]) == hzp.HZP_ERR_NOMEM         # pool full: back pressure
+    assert status(sched.release, 0) == hzp.HZP_ERR_INVALID_ARG                # not acquired yet
+    sched.acquire(0)
+    assert status(sched.acquire, 0) == hzp.HZP_ERR_INVALID_ARG
+    sched.acquire(1)
+    sched.release(1)                                                          # out of order ...
+    assert status(sched.prefetch, 2, dshards[2]) == hzp.HZP_ERR_NOMEM         # ... the cycle's next slot is layer 0's
+    sched.release(0)
+    sched.prefetch(2, dshards[2])
+    ptr = sched.acquire(2)
+    torch.cuda.synchronize()
+    sched.drain()
+    got = to_host(view16(ptr, oplan["buckets"][2]["P"]).clone(), np.uint16)
+    assert np.array_equal(got, on.gather_concat(shards[2]))
+    sched.release(2)
+    sched.destroy()
+    with pytest.raises(hzp.HzpError):
+        hzp.Sched(plan, gather_slots=0)
+
+
+def test_hungry_reduce_after_the_producer_and_join():
+    say("scheduler: hungry reduce")
+    oplan, plan, _ = _layers(3, 52)
+    R, rank = 4, 5
+    rng = np.random.default_rng(53)
+    sched = hzp.Sched(plan, gather_slots=1, queue_capacity=16)
+    producer, consumer = torch.cuda.Stream(), torch.cuda.Stream()
+    host, dev, outs = [], [], []
+    busy = torch.randn(2048, 2048, device=DEV)
+    for layer, b in enumerate(oplan["buckets"]):
+        _, n = op.shard_range(oplan, b, 3, rank)
+        g = [hzp_inputs.to_bf16_bits((rng.standard_normal(n) * 1e-3).astype(np.float32)) for _ in range(R)]
+        host.append(g)
+        staged = [to_dev(x) for x in g]
+        slices = [torch.zeros(n, dtype=torch.int16, device=DEV) for _ in range(R)]
+        out = torch.full((n,), 3.0, device=DEV)
+        dev.append((staged, slices))
+        outs.append(out)
+    torch.cuda.synchronize()
+    want = [on.reduce(host[layer], scale=0.25) for layer in range(3)]
+    rounds = 12     # the reductions run beside a busy compute stream; repeat to vary the interleaving
+    for rnd in range(rounds):
+        for layer in range(3):
+            staged, slices = dev[layer]
+            with torch.cuda.stream(producer):
+                busy = busy @ busy * 1e-3             # the "backward pass" that produces the gradients
+                for dst, src in zip(slices, staged):
+                    dst.zero_()
+                    dst.copy_(src)
+            sched.reduce(layer, 3, rank, slices, 0.25, False, outs[layer], producer)
+        sched.join(consumer)
+        with torch.cuda.stream(consumer):
+            copies = [o.clone() for o in outs]
+            for o in outs:
+                o.fill_(3.0)
+        consumer.synchronize()
+        producer.wait_stream(consumer)
+        for layer in range(3):
+            got = to_host(copies[layer], np.float32)
+            bad = np.nonzero(got.view(np.uint32) != want[layer].view(np.uint32))[0]
+            assert bad.size == 0, (rnd, layer, bad.size, bad[:8].tolist(), got[bad[:8]].tolist(),
+                                   want[layer][bad[:8]].tolist())
+    assert sched.stats().reduces_issued == 3 * rounds
+    sched.destroy()
