@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
-                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate")
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,overlap")
     return ap.parse_args()
 
 
@@ -180,6 +180,97 @@ def time_secondary(w, hzp, torch, stream, phase, steps, warmup):
     e1.record(stream)
     stream.synchronize()
     return e0.elapsed_time(e1) / steps
+
+
+def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
+    """Secondary row for the asynchronous scheduler (Section 4.2): per-layer parameter gathers
+    prefetched `depth` layers ahead from the background thread into the cyclic pool, while the
+    main stream runs a synthetic compute kernel per layer sized to `compute_ratio` times a layer's
+    gather.  Compared with issuing the same gathers on the main stream in front of each layer's
+    compute.  Two kinds of compute: `spin` (one workgroup that only waits: no contention, shows
+    what the dispatch machinery itself hides) and `gemm` (bf16 4096^3 matmuls: a register-file
+    saturating MFMA kernel, beside which no other kernel can be resident on a CU)."""
+    import time as _time
+    n = w.n_layers
+    a = torch.randn(4096, 4096, device="cuda:0", dtype=torch.bfloat16)
+    b = torch.randn(4096, 4096, device="cuda:0", dtype=torch.bfloat16)
+    c = torch.empty(4096, 4096, device="cuda:0", dtype=torch.bfloat16)
+    s = stream.cuda_stream
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = _time.perf_counter()
+        for _ in range(rounds):
+            fn()
+        torch.cuda.synchronize()
+        return (_time.perf_counter() - t0) * 1e3 / rounds
+
+    def gathers_only():
+        for l, arr, dst in w.l3_args:
+            hzp.hzp_gather_layer(w.plan, l, 0, 3, arr, dst, None, stream=s)
+
+    def one_matmul():
+        with torch.cuda.stream(stream):
+            torch.matmul(a, b, out=c)
+
+    def one_spin():
+        with torch.cuda.stream(stream):
+            torch.cuda._sleep(1000000)
+
+    t_gather = timed(gathers_only)
+    per_layer = compute_ratio * t_gather / n
+    reps = max(1, int(round(per_layer / timed(one_matmul))))
+    cycles = int(1000000 * per_layer / timed(one_spin))
+
+    def make_compute(kind):
+        def compute(l):
+            with torch.cuda.stream(stream):
+                if kind == "gemm":
+                    for _ in range(reps):
+                        torch.matmul(a, b, out=c)
+                else:
+                    torch.cuda._sleep(cycles)
+        return compute
+
+    out = {"layers": n, "prefetch_depth": depth, "gather_only_ms": round(t_gather, 3), "cases": []}
+    for kind in ("spin", "gemm"):
+        compute = make_compute(kind)
+
+        def compute_only():
+            for l in range(n):
+                compute(l)
+
+        def serial():
+            for l, arr, dst in w.l3_args:
+                hzp.hzp_gather_layer(w.plan, l, 0, 3, arr, dst, None, stream=s)
+                compute(l)
+
+        sched = hzp.Sched(w.plan, gather_slots=depth, queue_capacity=2 * depth + 4)
+
+        def overlapped():
+            for l in range(min(depth, n)):
+                sched.prefetch(l, w.l3_args[l][1])
+            for l in range(n):
+                sched.acquire(l, s)
+                compute(l)
+                sched.release(l, s)
+                if l + depth < n:
+                    sched.prefetch(l + depth, w.l3_args[l + depth][1])
+            sched.join(s)
+
+        t_compute, t_serial, t_async = timed(compute_only), timed(serial), timed(overlapped)
+        sched.drain()
+        st = sched.stats()
+        out["cases"].append({
+            "compute": kind, "compute_only_ms": round(t_compute, 3),
+            "serial_ms": round(t_serial, 3), "scheduled_ms": round(t_async, 3),
+            "gather_time_hidden": round((t_serial - t_async) / t_gather, 3),
+            "acquire_host_wait_us_per_layer": round(st.acquire_host_wait_us / max(1, st.gathers_issued), 2)})
+        out.update(pool_bytes=st.pool_bytes, peak_live_bytes=st.peak_live_bytes,
+                   pool_unused_fraction_at_peak=round(1.0 - st.peak_live_bytes / st.pool_bytes, 4))
+        sched.destroy()
+    return out
 
 
 def run_step(w, hzp, step, stream, phases, events=None):
@@ -369,6 +460,9 @@ def main():
                      "gather_level3": round(g3_ms, 4)},
     }
     secondary = [x for x in args.secondary.split(",") if x]
+    if "overlap" in secondary:
+        secondary.remove("overlap")
+        result["scheduler_overlap"] = overlap_probe(w, hzp, torch, stream)
     if secondary:
         add_secondary_buffers(w, secondary)
         result["secondary"] = {}
