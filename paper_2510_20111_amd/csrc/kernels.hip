@@ -2,12 +2,14 @@
 //
 // Every kernel here streams: each byte is read once and written once, there is no reuse and
 // no contraction, so the bound is HBM bandwidth (26+2R bytes per element for the fused update
-// with bf16 gradients, against some tens of fp32 operations).  The design therefore is
+// with bf16 gradients, against about 30 fp32 operations).  The design therefore is
 //   - every load/store instruction of a wavefront covers one contiguous run of memory, and a
 //     lane requests all of its (R+3) x 2 input vectors before it uses the first one;
-//   - single-wavefront workgroups for the many-stream kernels (finer-grained dispatch keeps the
-//     15-19 address streams of the fused update moving together);
-//   - non-temporal loads and stores: nothing is touched twice, so no line should be kept;
+//   - single-wavefront workgroups, dispatched in address order, and for the many-stream fused
+//     update only about 5 of them resident per CU: a small, coherent front of in-flight
+//     groups serves the memory controllers better than full occupancy;
+//   - non-temporal loads, and stores that are written through to memory with the streaming
+//     hint: nothing is touched twice, so no line should be kept;
 //   - many layers per launch: shards of one layer are only a few MB, so the per-layer
 //     pointers travel in the kernel-argument block and one grid covers all of them;
 //   - consecutive workgroups take consecutive tiles.  The hardware deals workgroups to the
@@ -17,8 +19,9 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#ifdef HZP_TUNE
 #include <cstdlib>
-#include <cstring>
+#endif
 
 #include "hzp_internal.hpp"
 
@@ -31,16 +34,10 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
 typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
-
 template <class T>
 __device__ __forceinline__ T ld_stream(const T *p)
 {
     return __builtin_nontemporal_load(p);
-}
-template <class T>
-__device__ __forceinline__ void st_stream(T *p, T v)
-{
-    __builtin_nontemporal_store(v, p);
 }
 
 // Element (vector) `idx` of a stream whose base is uniform: base + 32-bit byte offset, so that the
@@ -430,7 +427,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) v
 
 // ---------------------------------------------------------------------------------------
 // Gather: concatenation of equal shards (16-byte vectors; everything is aligned).
-// grid = (tiles per shard, number of shards).
+// grid = (wavefront tiles per shard, number of shards).
 // ---------------------------------------------------------------------------------------
 struct ConcatArgs {
     const void *src[HZP_MAX_GROUP];
@@ -456,9 +453,10 @@ __global__ __launch_bounds__(kWave) void concat_kernel(const ConcatArgs a)
 // One single-wavefront workgroup per chunk of at most kUnpackChunk elements of one piece (a run of
 // one tensor inside one shard).  1024-element chunks measured fastest on MI355X (6.5-6.6 TB/s on
 // dense and MoE layers; 4096: 6.0, 16384: 5.4, 512: 5.3-6.0): like the plain copy, this kernel
-// wants little work per wavefront and every wave slot filled.  Sources are 16-byte aligned; a destination is only element-aligned, so a
-// chunk is written as: up to 15 bytes of single elements to reach a 16-byte boundary of the
-// destination, whole 16-byte vectors (whose source is then read unaligned), single elements.
+// wants little work per wavefront and every wave slot filled.  Sources are 16-byte aligned; a
+// destination is only element-aligned, so a chunk is written as: up to 15 bytes of single
+// elements to reach a 16-byte boundary of the destination, whole 16-byte vectors (whose source is
+// then read unaligned), single elements.
 // ---------------------------------------------------------------------------------------
 constexpr int kUnpackTensorCap = 400;
 struct UnpackArgs {
