@@ -227,7 +227,8 @@ hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint3
  *                NULL at level 3 when tensor_out is given
  *   tensor_out : level 3 only, may be NULL; host array [n_tensors of the bucket] of device
  *                pointers, each to numel_t elements, element-aligned only
- * At least one output is required; outputs must not overlap inputs.
+ * At least one output is required; outputs must not overlap inputs.  With both outputs the shards
+ * are read twice (one copy kernel per output).
  * Errors: INVALID_ARG (n_shards mismatch, no output, tensor_out at level 1), RANGE, UNSUPPORTED
  * (more than HZP_MAX_GROUP shards), ALIGN, NOMEM, HIP.
  * ------------------------------------------------------------------------------------------ */

@@ -119,3 +119,17 @@ def test_gather_argument_errors():
     assert _status(f, p, 1, 1, 3, [FAKE] * 2, FAKE, None, stream=0) == hzp.HZP_ERR_RANGE
     big = hzp.hzp_plan([1], [8 * 128], align=8, z3=128, z1=128)
     assert _status(f, big, 0, 0, 3, [FAKE] * 128, FAKE, None, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+
+
+def test_scheduler_argument_errors_before_any_gpu_call():
+    p = _plan()
+    for kw, want in [(dict(gather_slots=0), hzp.HZP_ERR_INVALID_ARG),
+                     (dict(queue_capacity=0), hzp.HZP_ERR_INVALID_ARG),
+                     (dict(cls=2), hzp.HZP_ERR_RANGE)]:
+        with pytest.raises(hzp.HzpError) as e:
+            hzp.Sched(p, **kw)
+        assert e.value.status == want
+    only_bf16 = hzp.hzp_plan([1], [64], align=8, z3=1, z1=1)
+    with pytest.raises(hzp.HzpError) as e:
+        hzp.Sched(only_bf16, cls=hzp.HZP_CLASS_F32)
+    assert e.value.status == hzp.HZP_ERR_RANGE
