@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
-                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,overlap")
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,perlayer,overlap")
     return ap.parse_args()
 
 
@@ -79,6 +79,7 @@ class Workload:
             return t
 
         self.keep = []
+        self.payload_params = 0           # tensor elements; the rest of p_total is padding
         g_ptrs, p_ptrs, m_ptrs, v_ptrs, o_ptrs = [], [], [], [], []
         self.l1_args, self.l3_args = [], []
         tid = 0
@@ -87,6 +88,7 @@ class Workload:
             for _ in range(b.n_tensors):
                 t = self.plan.tensor(tid)
                 ranges.append((t.offset, t.numel))
+                self.payload_params += t.numel
                 tid += 1
             beg, n = self.plan.shard(l, 0, 1, rank)
             o1, o3 = b.base // cfg["z1"], b.base // cfg["z3"]       # arena offsets of this bucket's slices
@@ -117,6 +119,10 @@ class Workload:
         self.unpack_args, self.reduce_args = None, None
         self.g_arr, self.p_arr = hzp.ptr_array(g_ptrs), hzp.ptr_array(p_ptrs)
         self.m_arr, self.v_arr, self.o_arr = hzp.ptr_array(m_ptrs), hzp.ptr_array(v_ptrs), hzp.ptr_array(o_ptrs)
+        # the same update as one call per layer (the secondary row "perlayer")
+        self.layer_args = [(l, hzp.ptr_array(g_ptrs[l * self.R:(l + 1) * self.R]), hzp.ptr_array([p_ptrs[l]]),
+                            hzp.ptr_array([m_ptrs[l]]), hzp.ptr_array([v_ptrs[l]]), hzp.ptr_array([o_ptrs[l]]))
+                           for l in range(n_layers)]
 
 
 def add_secondary_buffers(w, phases):
@@ -158,7 +164,12 @@ def add_secondary_buffers(w, phases):
 
 def run_secondary(w, hzp, stream, phase):
     s = stream.cuda_stream
-    if phase == "unpack":
+    if phase == "perlayer":
+        a = w.cfg["adamw"]
+        hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], w.cfg["grad_scale"], 1)
+        for l, g, p, m, v, o in w.layer_args:
+            hzp.hzp_adamw_shard(w.plan, l, l + 1, 0, w.rank, hy, g, w.R, p, m, v, o, stream=s)
+    elif phase == "unpack":
         for l, shards, tensors, _ in w.unpack_args:
             hzp.hzp_gather_layer(w.plan, l, 0, 3, shards, None, tensors, stream=s)
     elif phase == "accumulate":
@@ -323,7 +334,7 @@ def copy_probe(torch, hzp, stream):
 
 def cpu_baseline(w, torch, np):
     """The oracle, as it stands, on one layer's share of the same workload: reduce + AdamW on
-    the S1 shard, then both gathers for that layer; repeated for roughly 15 s."""
+    the S1 shard, then both gathers for that layer; repeated for roughly 12 s."""
     from oracle import numeric as on
     grads, p, m, v, out, owners, shard3, shards, bucket = w.keep[0]
     a = w.cfg["adamw"]
@@ -347,7 +358,7 @@ def cpu_baseline(w, torch, np):
     t0 = time.perf_counter()
     one_pass(1)
     first = time.perf_counter() - t0
-    reps = max(1, min(20, int(15.0 / max(first, 1e-3))))
+    reps = max(1, min(200, int(12.0 / max(first, 1e-3))))
     t0 = time.perf_counter()
     for r in range(reps):
         one_pass(2 + r)
@@ -450,6 +461,7 @@ def main():
                                "reduce+AdamW on the S1 shards + level-1 gather + level-3 gather"
                                % (cfg["name"], w.n_layers, R, w.z3, cfg["z1"], cfg["align"], rank),
                    "shard_params_per_step": w.s1_total, "padded_params": w.p_total,
+                   "payload_params": w.payload_params, "padding_params": w.p_total - w.payload_params,
                    "phases": sorted(phases)},
         "roofline": dominant,
         "rooflines": rooflines,
@@ -469,9 +481,11 @@ def main():
         for phase in secondary:
             ms = time_secondary(w, hzp, torch, stream, phase, args.steps, args.warmup)
             nbytes = {"unpack": lambda: 4 * w.payload_total, "reduce": lambda: (2 * R + 4) * w.s3_total,
-                      "accumulate": lambda: (4 * R + 8) * w.s3_total}[phase]()
+                      "accumulate": lambda: (4 * R + 8) * w.s3_total,
+                      "perlayer": lambda: fused_bytes}[phase]()
             kname = {"unpack": "unpack_kernel<2>", "reduce": "reduce_kernel<bf16,R=%d>" % R,
-                     "accumulate": "reduce_kernel<f32,R=%d,accumulate>" % R}[phase]
+                     "accumulate": "reduce_kernel<f32,R=%d,accumulate>" % R,
+                     "perlayer": "fused_adamw_kernel<R=%d,bf16>, one call per layer" % R}[phase]
             result["secondary"][phase] = roof(kname, nbytes, ms, w.n_layers, "%s_%s" % (phase, cfg["name"]))
             result["secondary"][phase].pop("share_of_step_time")
     if not args.no_probe:
