@@ -149,6 +149,17 @@ def gather_concat(srcs):
     return dst
 
 
+def gather_shard(zero1_pieces, j, z3):
+    """ZeRO-3 shard j of the bucket whose ZeRO-1 shards are `zero1_pieces` (all Z1 of them, in shard
+    order): the bucket is their concatenation and shard j is its j-th of z3 equal parts.  This is the
+    post-step parameter gather (Section 4.1.2, "Optimizer Step") for group sizes that need not nest."""
+    bucket = gather_concat(zero1_pieces)
+    if bucket.size % z3:
+        raise ValueError("bucket length is not a multiple of Z3")
+    S3 = bucket.size // z3
+    return bucket[j * S3:(j + 1) * S3].copy()
+
+
 def unpack_tensor(shards, offset, numel):
     """Copy tensor elements [offset, offset+numel) of the bucket out of its Z3 shards."""
     dt = shards[0].dtype

@@ -18,14 +18,18 @@ What the paper fixes (Section 4.1.1, Table 1 and the M_hzp equation):
 
 What the paper leaves open and this oracle fixes (each is a stated reading):
   * one flat bucket per (layer, dtype class); every tensor starts on a multiple
-    of A elements; the bucket is zero-padded to a multiple of A*Z1;
-  * Z3 divides Z1 (true of every configuration the paper reports) and Z2 is
-    Z3;  K = Z1 / Z3;
-  * rank rho in [0, Z1): ZeRO-3 index j = rho mod Z3 (consecutive ranks form
-    the parameter group, i.e. it sits inside a node), outer index
-    k = rho div Z3, ZeRO-1 shard i = j*K + k, so ZeRO-1 shard i lies inside
-    ZeRO-3 shard j and the post-step gather (Section 4.1.2, "Optimizer Step")
-    is a contiguous concatenation.
+    of A elements; the bucket is zero-padded to a multiple of A*lcm(Z1,Z2,Z3),
+    so that the shards of every level are whole multiples of A;
+  * the three group sizes are free (Section 4.1.1: they "can be arbitrarily
+    specified").  Every configuration the paper reports has Z2 = Z3 and
+    Z3 | Z1; then lcm = Z1, K = Z1 / Z3 and, for rank rho in [0, Z1):
+    ZeRO-3 index j = rho mod Z3 (consecutive ranks form the parameter group,
+    i.e. it sits inside a node), outer index k = rho div Z3, ZeRO-1 shard
+    i = j*K + k, so ZeRO-1 shard i lies inside ZeRO-3 shard j and the post-step
+    gather (Section 4.1.2, "Optimizer Step") is a contiguous concatenation;
+  * in general a rank rho in [0, lcm) owns one shard per level, chosen so that
+    every window of Z consecutive ranks holds each shard of that level once and
+    shards nest wherever one group size divides the next (see level_index).
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this.
 """
@@ -64,10 +68,10 @@ def make_plan(tensors_per_layer, tensor_numel, align, z3, z1, z2=0,
         raise PlanError("tensor_numel must hold one positive count per tensor")
     if not is_pow2(align) or align < 8:
         raise PlanError("alignment must be a power of two >= 8")
-    if z3 < 1 or z1 < 1 or z1 % z3 != 0:
-        raise PlanError("need Z3 >= 1 and Z3 | Z1")
-    if z2 not in (0, z3):
-        raise PlanError("Z2 must equal Z3 (0 means: same as Z3)")
+    if z3 < 1 or z1 < 1 or z2 < 0:
+        raise PlanError("group sizes must be positive (Z2 = 0 means: same as Z3)")
+    if z2 == 0:
+        z2 = z3
     if tensor_class is None:
         tensor_class = [CLASS_BF16] * n_tensors
     if tensor_wd_mult is None:
@@ -75,7 +79,8 @@ def make_plan(tensors_per_layer, tensor_numel, align, z3, z1, z2=0,
     if any(c not in (CLASS_BF16, CLASS_F32) for c in tensor_class):
         raise PlanError("unknown tensor class")
 
-    K = z1 // z3
+    K = z1 // z3 if z1 % z3 == 0 else 0     # only defined when ZeRO-1 shards nest in ZeRO-3 shards
+    world = lcm3(z1, z2, z3)                # number of ranks after which the ownership pattern repeats
     buckets = []          # in (layer, class) order
     tensors = [None] * n_tensors
     base = 0
@@ -95,13 +100,19 @@ def make_plan(tensors_per_layer, tensor_numel, align, z3, z1, z2=0,
                                   bucket=len(buckets))
                 payload_end = off + tensor_numel[t]
                 off = round_up(payload_end, align)
-            P = round_up(payload_end, align * z1)
+            P = round_up(payload_end, align * world)
             buckets.append(dict(layer=layer, cls=cls, tensor_ids=members,
                                 payload_end=payload_end, P=P,
-                                S3=P // z3, S1=P // z1, base=base))
+                                S3=P // z3, S2=P // z2, S1=P // z1, base=base))
             base += P
-    return dict(align=align, z3=z3, z2=z3, z1=z1, K=K, n_layers=n_layers,
+    return dict(align=align, z3=z3, z2=z2, z1=z1, K=K, world=world, n_layers=n_layers,
                 buckets=buckets, tensors=tensors, total_padded=base)
+
+
+def lcm3(a, b, c):
+    from math import gcd
+    ab = a * b // gcd(a, b)
+    return ab * c // gcd(ab, c)
 
 
 def find_bucket(plan, layer, cls):
@@ -111,28 +122,72 @@ def find_bucket(plan, layer, cls):
     return None
 
 
-def rank_to_indices(plan, rank):
-    """rank -> (j, k, i): ZeRO-3 index, outer index, ZeRO-1 shard index."""
-    z3, z1, K = plan["z3"], plan["z1"], plan["K"]
-    if not (0 <= rank < z1):
+def level_index(plan, level, rank):
+    """Index of the shard that `rank` owns at `level` (3 parameters, 2 gradients, 1 optimizer states).
+
+    The index depends on rank mod Z_level only, one-to-one.  Where a smaller group size divides
+    this level's, the shard is placed inside the rank's shard of that smaller group (mixed radix:
+    parent index first, then the rank's position among the parent's co-owners):
+        level 3:  j3 = rho mod Z3
+        level 2:  Z3 | Z2:  j2 = j3*(Z2/Z3) + (rho div Z3) mod (Z2/Z3)      else  j2 = rho mod Z2
+        level 1:  Z3 | Z2 | Z1:  i = j2*(Z1/Z2) + (rho div Z2) mod (Z1/Z2)
+                  else Z3 | Z1:  i = j3*(Z1/Z3) + (rho div Z3) mod (Z1/Z3)
+                  else Z2 | Z1:  i = j2*(Z1/Z2) + (rho div Z2) mod (Z1/Z2)
+                  else           i = rho mod Z1
+    """
+    z1, z2, z3 = plan["z1"], plan["z2"], plan["z3"]
+    if not (0 <= rank < plan["world"]):
         raise PlanError("rank out of range")
-    j = rank % z3
-    k = rank // z3
-    return j, k, j * K + k
+    j3 = rank % z3
+    if level == 3:
+        return j3
+    chain32 = z2 % z3 == 0
+    j2 = j3 * (z2 // z3) + (rank // z3) % (z2 // z3) if chain32 else rank % z2
+    if level == 2:
+        return j2
+    if level != 1:
+        raise PlanError("level must be 1, 2 or 3")
+    if z1 % z3 == 0 and not (chain32 and z1 % z2 == 0):
+        return j3 * (z1 // z3) + (rank // z3) % (z1 // z3)
+    if z1 % z2 == 0:
+        return j2 * (z1 // z2) + (rank // z2) % (z1 // z2)
+    return rank % z1
+
+
+def rank_to_indices(plan, rank):
+    """rank -> (j, k, i): ZeRO-3 index, outer index, ZeRO-1 shard index (k is 0 when Z3 does not divide Z1)."""
+    j, i = level_index(plan, 3, rank), level_index(plan, 1, rank)
+    k = i - j * plan["K"] if plan["K"] else 0
+    return j, k, i
 
 
 def shard_range(plan, bucket, level, rank):
     """(begin, length) in bucket-relative elements of the rank's shard.
 
-    level 3: the parameter/gradient shard (group size Z3);
-    level 1: the optimizer-state shard (group size Z1).
+    level 3: the parameter shard (group size Z3); level 2: the gradient shard (Z2);
+    level 1: the optimizer-state shard (Z1).
     """
-    j, k, i = rank_to_indices(plan, rank)
-    if level == 3:
-        return j * bucket["S3"], bucket["S3"]
-    if level == 1:
-        return i * bucket["S1"], bucket["S1"]
-    raise PlanError("level must be 1 or 3")
+    if level not in (1, 2, 3):
+        raise PlanError("level must be 1, 2 or 3")
+    length = bucket["S%d" % level]
+    return level_index(plan, level, rank) * length, length
+
+
+def cover(plan, bucket, j):
+    """ZeRO-1 shards that meet ZeRO-3 shard j, in order: [(i, src_off, dst_off, length)].
+
+    src_off is relative to ZeRO-1 shard i, dst_off to ZeRO-3 shard j.  This is what the post-step
+    parameter gather (Section 4.1.2, "Optimizer Step") has to place when the two levels do not
+    nest; with Z3 | Z1 it is the K whole shards j*K .. j*K+K-1.
+    """
+    S1, S3 = bucket["S1"], bucket["S3"]
+    lo3, hi3 = j * S3, (j + 1) * S3
+    out = []
+    for i in range(plan["z1"]):
+        lo, hi = max(lo3, i * S1), min(hi3, (i + 1) * S1)
+        if lo < hi:
+            out.append((i, lo - i * S1, lo - lo3, hi - lo))
+    return out
 
 
 def per_rank_bytes(plan):

@@ -369,3 +369,23 @@ def test_gather_of_shards_is_identity_and_unpack_inverts_pack():
         assert got.tolist() == want
     with pytest.raises(ValueError):
         on.unpack_tensor(shards3, b["P"] - 3, 4)
+
+
+def test_gather_shard_free_group_sizes_brute_force():
+    """Shard j rebuilt from all ZeRO-1 pieces equals the element-by-element walk
+    bucket[j*S3 + x] = piece[(j*S3 + x) // S1][(j*S3 + x) % S1], and equals placing the
+    pieces the planner's cover lists -- for group sizes that do not nest."""
+    rng = np.random.default_rng(13)
+    for z1, z2, z3 in [(6, 2, 4), (2, 4, 4), (5, 3, 2), (8, 4, 2), (3, 3, 7)]:
+        plan = op.make_plan([2], [37, 150], 8, z3, z1, z2)
+        b = plan["buckets"][0]
+        S1, S3 = b["S1"], b["S3"]
+        pieces = [rng.integers(0, 1 << 16, size=S1).astype(np.uint16) for _ in range(z1)]
+        for j in range(z3):
+            got = on.gather_shard(pieces, j, z3)
+            want = [int(pieces[(j * S3 + x) // S1][(j * S3 + x) % S1]) for x in range(S3)]
+            assert got.tolist() == want
+            placed = np.zeros(S3, dtype=np.uint16)
+            for i, src, dst, n in op.cover(plan, b, j):
+                placed[dst:dst + n] = pieces[i][src:src + n]
+            assert np.array_equal(placed, got)

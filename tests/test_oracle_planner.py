@@ -124,6 +124,7 @@ def test_per_rank_bytes_match_memory_model(d):
     z1, z3 = plan["z1"], plan["z3"]
     assert Fraction(opt + grad + par) == (Fraction(12 * Ptot, z1) + Fraction(4 * Ptot, z3)
                                           + Fraction(2 * Ptot, z3))
+    assert opt + grad + par == op.hzp_memory_bytes(Ptot, z1, z3, z3)
     assert opt == 12 * Ptot // z1 and grad == 4 * Ptot // z3 and par == 2 * Ptot // z3
     if z1 == z3:                                             # collapses to 18N/Z (ZP) ...
         assert opt + grad + par == 18 * Ptot // z1
@@ -177,7 +178,7 @@ def test_rank_map_example():
 
 
 @pytest.mark.parametrize("bad", [
-    dict(align=12), dict(align=4), dict(z3=3, z1=8), dict(z3=0), dict(z2=4),
+    dict(align=12), dict(align=4), dict(z3=0), dict(z1=0), dict(z2=-1),
     dict(tensor_numel=[0, 5]), dict(tensors_per_layer=[0, 2]), dict(tensor_class=[0, 2]),
 ])
 def test_rejects_bad_descriptors(bad):
@@ -185,6 +186,98 @@ def test_rejects_bad_descriptors(bad):
     d.update(bad)
     with pytest.raises(op.PlanError):
         op.make_plan(**d)
+
+
+# ------------------------------------------------------------------ free group sizes
+
+@st.composite
+def free_descriptors(draw, max_numel=400):
+    n_layers = draw(st.integers(1, 3))
+    tpl = [draw(st.integers(1, 4)) for _ in range(n_layers)]
+    n = sum(tpl)
+    z = st.integers(1, 9)
+    return dict(tensors_per_layer=tpl, tensor_numel=[draw(st.integers(1, max_numel)) for _ in range(n)],
+                align=draw(st.sampled_from([8, 16])), z3=draw(z), z2=draw(z), z1=draw(z))
+
+
+def test_free_group_sizes_hand_values():
+    for row in _rows("general_groups_hand_values.txt"):
+        kind, v = row[0], [int(x) for x in row[1:]]
+        if kind == "layout":
+            A, z1, z2, z3, payload, P, S1, S2, S3 = v
+            b = op.make_plan([1], [payload], A, z3, z1, z2)["buckets"][0]
+            assert (b["P"], b["S1"], b["S2"], b["S3"]) == (P, S1, S2, S3), row
+        elif kind == "rank":
+            z1, z2, z3, rho, j3, j2, i = v
+            plan = op.make_plan([1], [8], 8, z3, z1, z2)
+            assert [op.level_index(plan, l, rho) for l in (3, 2, 1)] == [j3, j2, i], row
+        else:
+            A, z1, z2, z3, payload, j = v[:6]
+            plan = op.make_plan([1], [payload], A, z3, z1, z2)
+            want = [tuple(v[6 + 4 * q:10 + 4 * q]) for q in range((len(v) - 6) // 4)]
+            assert op.cover(plan, plan["buckets"][0], j) == want, row
+
+
+@settings(max_examples=150, deadline=None)
+@given(free_descriptors())
+def test_free_group_sizes_ownership_by_enumeration(d):
+    """Every level: each aligned window of Z consecutive ranks owns every element exactly once;
+    shards nest where the group sizes divide; the cover equals element-by-element ownership."""
+    plan = op.make_plan(**d)
+    A = plan["align"]
+    Z = {1: plan["z1"], 2: plan["z2"], 3: plan["z3"]}
+    W = plan["world"]
+    assert all(W % z == 0 for z in Z.values()) and not any(
+        all(w % z == 0 for z in Z.values()) for w in range(1, W))          # least common multiple
+    for level, z in Z.items():
+        idx = [op.level_index(plan, level, r) for r in range(W)]
+        assert all(idx[r] == idx[r % z] for r in range(W))                 # depends on rank mod Z only
+        assert sorted(idx[:z]) == list(range(z))                           # one-to-one inside a group
+    for b in plan["buckets"]:
+        P = b["P"]
+        assert b["payload_end"] <= P < b["payload_end"] + A * W and P % (A * W) == 0
+        for level, z in Z.items():
+            S = b["S%d" % level]
+            assert S * z == P and S % A == 0
+            count = [0] * P
+            for r in range(z):                                             # one aligned window
+                beg, n = op.shard_range(plan, b, level, r)
+                assert n == S
+                for x in range(beg, beg + n):
+                    count[x] += 1
+            assert count == [1] * P
+
+        def inside(r, inner, outer):
+            bi, ni = op.shard_range(plan, b, inner, r)
+            bo, no = op.shard_range(plan, b, outer, r)
+            return bo <= bi and bi + ni <= bo + no
+        for r in range(W):
+            if Z[2] % Z[3] == 0:
+                assert inside(r, 2, 3)
+            if Z[1] % Z[3] == 0:
+                assert inside(r, 1, 3)
+            if Z[1] % Z[2] == 0 and (Z[2] % Z[3] == 0 or Z[1] % Z[3] != 0):
+                assert inside(r, 1, 2)
+        for j in range(Z[3]):
+            owner = {}
+            for x in range(j * b["S3"], (j + 1) * b["S3"]):                # element by element
+                owner.setdefault(x // b["S1"], []).append(x)
+            want = [(i, xs[0] - i * b["S1"], xs[0] - j * b["S3"], len(xs)) for i, xs in sorted(owner.items())]
+            assert op.cover(plan, b, j) == want
+    opt, grad, par = op.per_rank_bytes(plan)
+    if all(c == 0 for c in [plan["tensors"][t]["cls"] for t in range(len(plan["tensors"]))]):
+        assert opt + grad + par == op.hzp_memory_bytes(plan["total_padded"], Z[1], Z[2], Z[3])
+
+
+def test_free_group_sizes_reduce_to_the_nested_map():
+    """With Z2 = Z3 | Z1 the general rule is the nested one: j = r mod Z3, i = j*K + r div Z3."""
+    for z3, K in [(1, 1), (2, 3), (8, 8), (4, 4), (3, 5)]:
+        plan = op.make_plan([1], [64], 8, z3, z3 * K)
+        assert plan["world"] == z3 * K and plan["K"] == K and plan["z2"] == z3
+        for r in range(z3 * K):
+            assert op.level_index(plan, 3, r) == r % z3 == op.level_index(plan, 2, r)
+            assert op.level_index(plan, 1, r) == (r % z3) * K + r // z3
+            assert op.rank_to_indices(plan, r) == (r % z3, r // z3, (r % z3) * K + r // z3)
 
 
 # ------------------------------------------------------------------ hand-worked model shapes
