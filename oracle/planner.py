@@ -219,3 +219,24 @@ def owner_tensor(plan, bucket, pos):
         if rec["offset"] <= pos < rec["offset"] + rec["numel"]:
             return t
     return -1
+
+
+def choose_groups(N, dp, node, budget_bytes):
+    """Least sharding whose static memory M_hzp fits `budget_bytes`: (z1, z2, z3) or None.
+
+    The paper sets the group sizes "according to the available device memory" and keeps parameters
+    and gradients inside a node (Section 3.1, Section 4.1.1) but gives no procedure; this is the
+    reading used here.  Candidates: Z3 divides `node` (parameter groups tile a node) and Z2 = Z3;
+    Z3 | Z1 | dp.  Among the candidates with 12N/Z1 + 4N/Z2 + 2N/Z3 <= budget the one with the
+    smallest Z3 wins (least parameter all-gather per layer), then the smallest Z1.
+    """
+    best = None
+    for z3 in range(1, node + 1):
+        if node % z3 or dp % z3:
+            continue
+        for z1 in range(z3, dp + 1, z3):
+            if dp % z1:
+                continue
+            if hzp_memory_bytes(N, z1, z3, z3) <= budget_bytes and (best is None or (z3, z1) < best):
+                best = (z3, z1)
+    return None if best is None else (best[1], best[0], best[0])

@@ -280,6 +280,23 @@ def test_free_group_sizes_reduce_to_the_nested_map():
             assert op.rank_to_indices(plan, r) == (r % z3, r // z3, (r % z3) * K + r // z3)
 
 
+def test_choose_groups_hand_values_and_optimality():
+    for row in _rows("choose_groups.txt"):
+        N, dp, node, budget = (int(x) for x in row[:4])
+        want = None if row[4] == "none" else tuple(int(x) for x in row[4:7])
+        assert op.choose_groups(N, dp, node, budget) == want, row
+    # whatever is chosen fits, and no admissible candidate with a smaller (Z3, Z1) does
+    for N, dp, node, budget in [(12345, 48, 8, 30000), (10 ** 9, 256, 8, 3 * 10 ** 9), (999, 36, 6, 4000)]:
+        z1, z2, z3 = op.choose_groups(N, dp, node, budget)
+        assert z2 == z3 and node % z3 == 0 and z1 % z3 == 0 and dp % z1 == 0
+        assert 12 * N * z3 + 6 * N * z1 <= budget * z1 * z3                       # M_hzp <= budget, in integers
+        for c3 in range(1, node + 1):
+            for c1 in range(1, dp + 1):
+                admissible = node % c3 == 0 and c1 % c3 == 0 and dp % c1 == 0
+                if admissible and (c3, c1) < (z3, z1):
+                    assert 12 * N * c3 + 6 * N * c1 > budget * c1 * c3, (c3, c1)
+
+
 # ------------------------------------------------------------------ hand-worked model shapes
 
 def _first_bucket_named(cfg, plan, layer_name):
