@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
-                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,perlayer,overlap")
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,perlayer,freegroups,overlap")
     return ap.parse_args()
 
 
@@ -152,6 +152,23 @@ def add_secondary_buffers(w, phases):
                       for r in range(w.R)]
             acc = w._piece("acc", w.s3_total, torch.float32, o3, b.s3).zero_()
             w.accum_args.append((l, hzp.ptr_array(slices), acc, slices))
+    if "freegroups" in phases and getattr(w, "free_args", None) is None:
+        # the same layers under group sizes that do not nest (Z1 = 3*Z3/2): ZeRO-3 shard 1 of every
+        # layer is rebuilt from one partial and one whole ZeRO-1 shard
+        cfg = w.cfg
+        tpl = cfg["tensors_per_layer"][:w.n_layers]
+        w.free_z1 = max(3, 3 * cfg["z3"] // 2)
+        w.free_plan = hzp.hzp_plan(tpl, cfg["tensor_numel"][:sum(tpl)], cfg["align"], cfg["z3"], w.free_z1)
+        fb = [w.free_plan.bucket(l, 0) for l in range(w.n_layers)]
+        w.free_s3_total = sum(b.s3 for b in fb)
+        s1_total = sum(b.s1 for b in fb)
+        w.free_args, off1, off3 = [], 0, 0
+        for l, b in enumerate(fb):
+            first, n = w.free_plan.cover(l, 0, 1)
+            owners = [w._piece("fo%d" % q, s1_total, bf16, off1, b.s1).normal_() for q in range(n)]
+            dst = w._piece("fs3", w.free_s3_total, bf16, off3, b.s3)
+            w.free_args.append((l, hzp.ptr_array(owners), dst, owners))
+            off1, off3 = off1 + b.s1, off3 + b.s3
     if "reduce" in phases and w.reduce_args is None:
         w.reduce_args = []
         for l, b in enumerate(w.buckets):
@@ -169,6 +186,9 @@ def run_secondary(w, hzp, stream, phase):
         hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], w.cfg["grad_scale"], 1)
         for l, g, p, m, v, o in w.layer_args:
             hzp.hzp_adamw_shard(w.plan, l, l + 1, 0, w.rank, hy, g, w.R, p, m, v, o, stream=s)
+    elif phase == "freegroups":
+        for l, owners, dst, _ in w.free_args:
+            hzp.hzp_gather_shard(w.free_plan, l, 0, 1, owners, dst, stream=s)
     elif phase == "unpack":
         for l, shards, tensors, _ in w.unpack_args:
             hzp.hzp_gather_layer(w.plan, l, 0, 3, shards, None, tensors, stream=s)
@@ -482,10 +502,12 @@ def main():
             ms = time_secondary(w, hzp, torch, stream, phase, args.steps, args.warmup)
             nbytes = {"unpack": lambda: 4 * w.payload_total, "reduce": lambda: (2 * R + 4) * w.s3_total,
                       "accumulate": lambda: (4 * R + 8) * w.s3_total,
-                      "perlayer": lambda: fused_bytes}[phase]()
+                      "perlayer": lambda: fused_bytes, "freegroups": lambda: 4 * w.free_s3_total}[phase]()
             kname = {"unpack": "unpack_kernel<2>", "reduce": "reduce_kernel<bf16,R=%d>" % R,
                      "accumulate": "reduce_kernel<f32,R=%d,accumulate>" % R,
-                     "perlayer": "fused_adamw_kernel<R=%d,bf16>, one call per layer" % R}[phase]
+                     "perlayer": "fused_adamw_kernel<R=%d,bf16>, one call per layer" % R,
+                     "freegroups": "concat_ranges_kernel (Z1=%d over Z3=%d: ZeRO-3 shard from partial owners)"
+                                   % (getattr(w, "free_z1", 0), w.z3)}[phase]
             result["secondary"][phase] = roof(kname, nbytes, ms, w.n_layers, "%s_%s" % (phase, cfg["name"]))
             result["secondary"][phase].pop("share_of_step_time")
     if not args.no_probe:

@@ -73,13 +73,28 @@ typedef enum { HZP_GRAD_DEFAULT = 0, HZP_GRAD_BF16 = 1, HZP_GRAD_F32 = 2 } hzp_g
  * one flat bucket per (layer, class):
  *     off_0 = 0,  off_{t+1} = round_up(off_t + n_t, A)        every tensor starts A-aligned
  *     payload_end = off_last + n_last
- *     P  = round_up(payload_end, A*Z1)                         padded length (padding holds 0)
- *     S3 = P/Z3   ZeRO-3 shard j covers [j*S3, (j+1)*S3)       parameters, gradients
- *     S1 = P/Z1   ZeRO-1 shard i covers [i*S1, (i+1)*S1)       master, momentum, variance
- *     rank r in [0,Z1):  j = r mod Z3,  k = r div Z3,  i = j*K + k,  K = Z1/Z3
+ *     P  = round_up(payload_end, A*lcm(Z1,Z2,Z3))              padded length (padding holds 0)
+ *     S3 = P/Z3   ZeRO-3 shard j covers [j*S3, (j+1)*S3)       parameters          (level 3)
+ *     S2 = P/Z2   gradient shard s covers [s*S2, (s+1)*S2)     fp32 gradients      (level 2)
+ *     S1 = P/Z1   ZeRO-1 shard i covers [i*S1, (i+1)*S1)       master, momentum, variance (level 1)
+ * Every shard length is a multiple of A.  The paper's configurations all have Z2 = Z3 | Z1; then
+ * lcm = Z1 and, with K = Z1/Z3,
+ *     rank r in [0,Z1):  j = r mod Z3,  k = r div Z3,  i = j*K + k
  * so ZeRO-1 shard i lies inside ZeRO-3 shard j, and the K owners of one ZeRO-3 shard are the
- * ranks j, j+Z3, j+2*Z3, ...  Buckets are ordered by (layer, class); `base` is the running sum
- * of P in that order.
+ * ranks j, j+Z3, j+2*Z3, ...
+ *
+ * Section 4.1.1 leaves the three sizes free.  In general a rank r in [0, lcm(Z1,Z2,Z3)) owns the
+ * shard with this index at each level (it depends on r mod Z_level only, one-to-one, and a shard
+ * lies inside the rank's shard of a smaller group wherever that group's size divides its own):
+ *     level 3:  j3 = r mod Z3
+ *     level 2:  Z3 | Z2:       j2 = j3*(Z2/Z3) + (r div Z3) mod (Z2/Z3)     else  j2 = r mod Z2
+ *     level 1:  Z3 | Z2 | Z1:  i  = j2*(Z1/Z2) + (r div Z2) mod (Z1/Z2)
+ *               else Z3 | Z1:  i  = j3*(Z1/Z3) + (r div Z3) mod (Z1/Z3)
+ *               else Z2 | Z1:  i  = j2*(Z1/Z2) + (r div Z2) mod (Z1/Z2)
+ *               else           i  = r mod Z1
+ * When Z3 does not divide Z1 a ZeRO-3 shard is covered by whole and partial ZeRO-1 shards
+ * (hzp_plan_cover, hzp_gather_shard).  Buckets are ordered by (layer, class); `base` is the running
+ * sum of P in that order.
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
     uint32_t n_layers;                  /* >= 1 */
@@ -88,12 +103,14 @@ typedef struct {
     const uint8_t *tensor_class;        /* host array of hzp_class_t per tensor; NULL: all BF16 */
     const float *tensor_wd_mult;        /* host array, multiplies weight_decay per tensor; NULL: all 1 */
     uint32_t align_elems;               /* A: power of two, >= 8 */
-    uint32_t z3, z2, z1;                /* z2 is 0 or equal to z3; z3 must divide z1 */
+    uint32_t z3, z2, z1;                /* each >= 1 and free; z2 == 0 means z2 = z3 */
 } hzp_plan_desc_t;
 
 typedef struct {
     uint32_t n_layers, n_buckets, n_tensors;
-    uint32_t align_elems, z3, z2, z1, k;    /* k = z1 / z3 */
+    uint32_t align_elems, z3, z2, z1;
+    uint32_t k;                              /* z1 / z3, or 0 when z3 does not divide z1 */
+    uint32_t world;                          /* lcm(z1, z2, z3): ranks are 0 .. world-1 */
     uint64_t total_padded;                   /* sum of P over all buckets */
 } hzp_plan_info_t;
 
@@ -107,6 +124,7 @@ typedef struct {
     uint64_t s3;                /* P / Z3 */
     uint64_t s1;                /* P / Z1 */
     uint64_t base;              /* start of the bucket in the global flat address space */
+    uint64_t s2;                /* P / Z2 */
 } hzp_bucket_info_t;
 
 typedef struct {
@@ -122,7 +140,7 @@ typedef struct {
 /* Build a plan.  Pure 64-bit integer work on the host: makes no HIP call and needs no GPU.
  * Copies everything it needs from `desc`.  *out is owned by the library until hzp_plan_free.
  * Errors: INVALID_ARG (NULL, zero counts, bad alignment, unknown class), UNSUPPORTED
- * (z3 does not divide z1, z2 not in {0, z3}), NOMEM. */
+ * (lcm(z1, z2, z3) or the tensor count exceeds 32 bits), NOMEM. */
 hzp_status_t hzp_plan(const hzp_plan_desc_t *desc, hzp_plan_t **out);
 
 /* Free a plan and its device tables.  NULL is allowed.  The caller must make sure that no kernel
@@ -134,10 +152,18 @@ hzp_status_t hzp_plan_info(const hzp_plan_t *plan, hzp_plan_info_t *out);
 /* RANGE if the layer has no bucket of that class. */
 hzp_status_t hzp_plan_bucket(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, hzp_bucket_info_t *out);
 hzp_status_t hzp_plan_tensor(const hzp_plan_t *plan, uint32_t tensor_id, hzp_tensor_info_t *out);
-/* rank -> ZeRO-3 index j, outer index k, ZeRO-1 shard index i. */
+/* rank -> ZeRO-3 index j, outer index k = i - j*K (0 when z3 does not divide z1), ZeRO-1 shard
+ * index i.  Outputs may be NULL.  RANGE if rank >= world. */
 hzp_status_t hzp_plan_rank(const hzp_plan_t *plan, uint32_t rank, uint32_t *j, uint32_t *k, uint32_t *i);
-/* Bucket-relative [begin, begin+len) of the rank's shard; level 3: parameter / gradient shard,
- * level 1: optimizer-state shard. */
+/* Index of the shard the rank owns at `level` (1, 2 or 3), by the rule above. */
+hzp_status_t hzp_plan_index(const hzp_plan_t *plan, int level, uint32_t rank, uint32_t *index);
+/* The ZeRO-1 shards that meet ZeRO-3 shard j of a bucket: first_owner .. first_owner+n_owners-1
+ * (consecutive shard indices; the first and the last may lie only partly inside shard j).  With
+ * z3 | z1 these are the K whole shards j*K .. j*K+K-1. */
+hzp_status_t hzp_plan_cover(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, uint32_t j,
+                            uint32_t *first_owner, uint32_t *n_owners);
+/* Bucket-relative [begin, begin+len) of the rank's shard; level 3: parameter shard, level 2:
+ * gradient shard, level 1: optimizer-state shard. */
 hzp_status_t hzp_plan_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level, uint32_t rank,
                             uint64_t *begin, uint64_t *len);
 /* Bytes one rank holds: 12*S1 of optimizer state, 4*P/Z2 of fp32 gradient and the parameter
@@ -152,6 +178,17 @@ hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt_bytes, uint64_
  * Errors: INVALID_ARG (NULL output, a group size of 0), UNSUPPORTED (result exceeds 64 bits). */
 hzp_status_t hzp_memory_model(uint64_t n_params, uint32_t z1, uint32_t z2, uint32_t z3, uint64_t *bytes);
 
+/* Least sharding whose M_hzp fits a per-device budget.  The paper sets the group sizes according
+ * to the available device memory and keeps parameters and gradients inside a node (Section 3.1,
+ * Section 4.1.1) without giving a procedure; this library's rule: candidates have Z2 = Z3 dividing
+ * both `node` (devices per node) and `dp`, and Z3 | Z1 | dp; among those with
+ * 12N/Z1 + 4N/Z2 + 2N/Z3 <= budget_bytes the smallest Z3 wins, then the smallest Z1.  Host-only.
+ * Errors: INVALID_ARG (NULL output, dp or node 0), NOMEM (no candidate fits the budget; the
+ * outputs then hold the most sharded candidate), UNSUPPORTED (dp above 2^20, or the model overflows
+ * 64 bits). */
+hzp_status_t hzp_choose_groups(uint64_t n_params, uint32_t dp, uint32_t node, uint64_t budget_bytes,
+                               uint32_t *z1, uint32_t *z2, uint32_t *z3);
+
 /* ------------------------------------------------------------------------------------------
  * Gradient reduction on the rank's shard: the arithmetic half of the per-layer reduce-scatter
  * ("performed using the float32 data type", Section 4.1.2, Backward Pass) together with the
@@ -160,8 +197,8 @@ hzp_status_t hzp_memory_model(uint64_t n_params, uint32_t z1, uint32_t z2, uint3
  *     s      = ((G_0[x] + G_1[x]) + G_2[x]) + ...      fp32, strictly in the order r = 0..R-1
  *     out[x] = accumulate ? out[x] + scale*s : scale*s  one multiply, one add, no fused rounding
  *
- * for x in [0, n), n = S1 (level 1) or S3 (level 3) of bucket (layer, cls).  The result equals
- * the scalar definition bit for bit.
+ * for x in [0, n), n = S1 (level 1), S2 (level 2) or S3 (level 3) of bucket (layer, cls).  The
+ * result equals the scalar definition bit for bit.
  *   grad_slices : host array [R] of device pointers; entry r points at element 0 of the rank's
  *                 slice inside contribution r, n elements of `grad_dtype`, 16-byte aligned
  *   R           : 1 .. HZP_MAX_REPLICAS
@@ -230,11 +267,32 @@ hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint3
  * At least one output is required; outputs must not overlap inputs.  With both outputs the shards
  * are read twice (one copy kernel per output).
  * Errors: INVALID_ARG (n_shards mismatch, no output, tensor_out at level 1), RANGE, UNSUPPORTED
- * (more than HZP_MAX_GROUP shards), ALIGN, NOMEM, HIP.
+ * (more than HZP_MAX_GROUP shards; level 1 on a plan whose z3 does not divide z1 -- use
+ * hzp_gather_shard), ALIGN, NOMEM, HIP.
  * ------------------------------------------------------------------------------------------ */
 hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level,
                               const void *const *shard_ptrs, uint32_t n_shards, void *bucket_out,
                               void *const *tensor_out, hipStream_t stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Post-step parameter gather for free group sizes (Section 4.1.1: the three sizes are independent;
+ * Section 4.1.2 "Optimizer Step": updated parameters are gathered back into the parameter shards).
+ * Rebuilds ZeRO-3 shard j of bucket (layer, cls) from the ZeRO-1 shards that meet it:
+ *
+ *     shard_out[x] = owner_ptrs[i - first_owner][(j*S3 + x) - i*S1],   i = (j*S3 + x) div S1
+ *
+ * for x in [0, S3).  With z3 | z1 this is the level-1 hzp_gather_layer.
+ *   owner_ptrs : host array [n_owners] of device pointers; entry q points at element 0 of the WHOLE
+ *                ZeRO-1 shard first_owner+q (S1 elements; only the part inside shard j is read),
+ *                16-byte aligned; first_owner and n_owners are hzp_plan_cover's
+ *   shard_out  : device pointer to S3 elements, 16-byte aligned, not overlapping any input
+ * Bit copies; elements are bf16 (class BF16) or fp32 (class F32).
+ * Errors: INVALID_ARG (NULL, n_owners differs from the cover), RANGE (layer / class / j),
+ * UNSUPPORTED (more than HZP_MAX_GROUP owners), ALIGN, HIP.
+ * ------------------------------------------------------------------------------------------ */
+hzp_status_t hzp_gather_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, uint32_t j,
+                              const void *const *owner_ptrs, uint32_t n_owners, void *shard_out,
+                              hipStream_t stream);
 
 /* ------------------------------------------------------------------------------------------
  * Asynchronous scheduler: the multi-stream dispatch of Section 4.2 for the local halves of the

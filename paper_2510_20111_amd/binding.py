@@ -20,8 +20,9 @@ _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSU
                  "HZP_ERR_ALIGN", "HZP_ERR_NOMEM", "HZP_ERR_HIP"]
 
 EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
-           "hzp_plan_rank", "hzp_plan_shard", "hzp_plan_bytes", "hzp_reduce_shard",
-           "hzp_adamw_shard", "hzp_gather_layer", "hzp_last_error", "hzp_memory_model",
+           "hzp_plan_rank", "hzp_plan_index", "hzp_plan_cover", "hzp_plan_shard", "hzp_plan_bytes",
+           "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_shard", "hzp_last_error",
+           "hzp_memory_model", "hzp_choose_groups",
            "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_acquire",
            "hzp_sched_release", "hzp_sched_reduce", "hzp_sched_join", "hzp_sched_drain", "hzp_sched_stats"]
 
@@ -46,14 +47,15 @@ class PlanInfo(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_uint32), ("n_buckets", ctypes.c_uint32),
                 ("n_tensors", ctypes.c_uint32), ("align_elems", ctypes.c_uint32),
                 ("z3", ctypes.c_uint32), ("z2", ctypes.c_uint32), ("z1", ctypes.c_uint32),
-                ("k", ctypes.c_uint32), ("total_padded", ctypes.c_uint64)]
+                ("k", ctypes.c_uint32), ("world", ctypes.c_uint32), ("total_padded", ctypes.c_uint64)]
 
 
 class BucketInfo(ctypes.Structure):
     _fields_ = [("layer", ctypes.c_uint32), ("cls", ctypes.c_uint32),
                 ("n_tensors", ctypes.c_uint32), ("bucket_index", ctypes.c_uint32),
                 ("payload_end", ctypes.c_uint64), ("padded", ctypes.c_uint64),
-                ("s3", ctypes.c_uint64), ("s1", ctypes.c_uint64), ("base", ctypes.c_uint64)]
+                ("s3", ctypes.c_uint64), ("s1", ctypes.c_uint64), ("base", ctypes.c_uint64),
+                ("s2", ctypes.c_uint64)]
 
 
 class TensorInfo(ctypes.Structure):
@@ -104,6 +106,12 @@ def _load():
     L.hzp_plan_tensor.argtypes = [vp, u32, ctypes.POINTER(TensorInfo)]
     L.hzp_plan_rank.restype = ctypes.c_int
     L.hzp_plan_rank.argtypes = [vp, u32, u32p, u32p, u32p]
+    L.hzp_plan_index.restype = ctypes.c_int
+    L.hzp_plan_index.argtypes = [vp, ctypes.c_int, u32, u32p]
+    L.hzp_plan_cover.restype = ctypes.c_int
+    L.hzp_plan_cover.argtypes = [vp, u32, u32, u32, u32p, u32p]
+    L.hzp_gather_shard.restype = ctypes.c_int
+    L.hzp_gather_shard.argtypes = [vp, u32, u32, u32, vp, u32, vp, vp]
     L.hzp_plan_shard.restype = ctypes.c_int
     L.hzp_plan_shard.argtypes = [vp, u32, u32, ctypes.c_int, u32, u64p, u64p]
     L.hzp_plan_bytes.restype = ctypes.c_int
@@ -118,6 +126,8 @@ def _load():
     L.hzp_gather_layer.argtypes = [vp, u32, u32, ctypes.c_int, vp, u32, vp, vp, vp]
     L.hzp_memory_model.restype = ctypes.c_int
     L.hzp_memory_model.argtypes = [ctypes.c_uint64, u32, u32, u32, u64p]
+    L.hzp_choose_groups.restype = ctypes.c_int
+    L.hzp_choose_groups.argtypes = [ctypes.c_uint64, u32, u32, ctypes.c_uint64, u32p, u32p, u32p]
     L.hzp_sched_create.restype = ctypes.c_int
     L.hzp_sched_create.argtypes = [vp, ctypes.POINTER(SchedDesc), ctypes.POINTER(vp)]
     L.hzp_sched_destroy.restype = None
@@ -214,6 +224,16 @@ class Plan:
         _check(_L.hzp_plan_rank(self.handle, rank, ctypes.byref(j), ctypes.byref(k), ctypes.byref(i)))
         return j.value, k.value, i.value
 
+    def index(self, level, rank):
+        out = ctypes.c_uint32()
+        _check(_L.hzp_plan_index(self.handle, level, rank, ctypes.byref(out)))
+        return out.value
+
+    def cover(self, layer, cls, j):
+        first, n = ctypes.c_uint32(), ctypes.c_uint32()
+        _check(_L.hzp_plan_cover(self.handle, layer, cls, j, ctypes.byref(first), ctypes.byref(n)))
+        return first.value, n.value
+
     def shard(self, layer, cls, level, rank):
         b, n = ctypes.c_uint64(), ctypes.c_uint64()
         _check(_L.hzp_plan_shard(self.handle, layer, cls, level, rank, ctypes.byref(b), ctypes.byref(n)))
@@ -242,6 +262,14 @@ def hzp_memory_model(n_params, z1, z2, z3):
     out = ctypes.c_uint64()
     _check(_L.hzp_memory_model(n_params, z1, z2, z3, ctypes.byref(out)))
     return out.value
+
+
+def hzp_choose_groups(n_params, dp, node, budget_bytes):
+    """(z1, z2, z3) of the least sharding that fits; raises HzpError(HZP_ERR_NOMEM) if none does."""
+    z1, z2, z3 = ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_uint32()
+    _check(_L.hzp_choose_groups(n_params, dp, node, budget_bytes, ctypes.byref(z1), ctypes.byref(z2),
+                                ctypes.byref(z3)))
+    return z1.value, z2.value, z3.value
 
 
 def hzp_plan_free(plan):
@@ -276,6 +304,12 @@ def hzp_gather_layer(plan, layer, cls, level, shard_ptrs, bucket_out=None, tenso
                                len(arr) if n_shards is None else n_shards, _addr(bucket_out),
                                ptr_array(tensor_out) if tensor_out is not None else None,
                                _stream(stream)))
+
+
+def hzp_gather_shard(plan, layer, cls, j, owner_ptrs, shard_out, stream=None, n_owners=None):
+    arr = ptr_array(owner_ptrs)
+    _check(_L.hzp_gather_shard(plan.handle, layer, cls, j, arr, len(arr) if n_owners is None else n_owners,
+                               _addr(shard_out), _stream(stream)))
 
 
 class Sched:

@@ -24,15 +24,15 @@ extern "C" hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer,
         return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: NULL plan, slice array or output");
     const BucketRec *b = find_bucket(plan, layer, cls);
     if (!b) return fail(HZP_ERR_RANGE, "hzp_reduce_shard: no bucket (layer %u, class %u)", layer, cls);
-    if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_reduce_shard: rank %u of %u", rank, plan->z1);
-    if (level != 1 && level != 3)
-        return fail(HZP_ERR_RANGE, "hzp_reduce_shard: level %d is neither 1 nor 3", level);
+    if (rank >= plan->world) return fail(HZP_ERR_RANGE, "hzp_reduce_shard: rank %u of %u", rank, plan->world);
+    if (level < 1 || level > 3)
+        return fail(HZP_ERR_RANGE, "hzp_reduce_shard: level %d is not 1, 2 or 3", level);
     if (grad_dtype > HZP_GRAD_F32)
         return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: unknown gradient type %u", grad_dtype);
     if (R == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: R must be at least 1");
     if (R > HZP_MAX_REPLICAS)
         return fail(HZP_ERR_UNSUPPORTED, "hzp_reduce_shard: R=%u exceeds %u", R, HZP_MAX_REPLICAS);
-    const uint64_t n = level == 1 ? b->S1 : b->S3;
+    const uint64_t n = level == 1 ? b->S1 : level == 2 ? b->S2 : b->S3;
     if (n >= (1ull << 30)) return fail(HZP_ERR_UNSUPPORTED, "hzp_reduce_shard: shard of 2^30 elements or more");
     for (uint32_t r = 0; r < R; ++r) {
         if (!grad_slices[r]) return fail(HZP_ERR_INVALID_ARG, "hzp_reduce_shard: slice %u is NULL", r);
@@ -57,7 +57,7 @@ extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_b
     if (layer_end > plan->n_layers)
         return fail(HZP_ERR_RANGE, "hzp_adamw_shard: layer_end %u of %u", layer_end, plan->n_layers);
     if (cls > 1) return fail(HZP_ERR_RANGE, "hzp_adamw_shard: class %u", cls);
-    if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_adamw_shard: rank %u of %u", rank, plan->z1);
+    if (rank >= plan->world) return fail(HZP_ERR_RANGE, "hzp_adamw_shard: rank %u of %u", rank, plan->world);
     if (hy->step == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: step is 1-based");
     if (R > HZP_MAX_REPLICAS)
         return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: R=%u exceeds %u", R, HZP_MAX_REPLICAS);
@@ -65,7 +65,7 @@ extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_b
     const uint32_t per_layer = prereduced ? 1u : R;
     const bool g32 = prereduced || cls == HZP_CLASS_F32;
     const bool o32 = cls == HZP_CLASS_F32;
-    const uint64_t j = rank % plan->z3, k = rank / plan->z3;
+    const uint64_t shard_index = level_index(plan, 1, rank);
 
     std::vector<FusedSegment> segs;
     try {
@@ -86,7 +86,7 @@ extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_b
         f.n = b->S1;
         f.first_slot = b->first_slot;
         f.n_tensors = b->n_tensors;
-        f.shard_begin = (j * plan->K + k) * b->S1;
+        f.shard_begin = shard_index * b->S1;
         if (f.n >= (1ull << 30))
             return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: layer %u: shard of 2^30 elements or more", layer);
         if (!f.master || !f.m || !f.v)
@@ -116,6 +116,9 @@ extern "C" hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer,
     if (!b) return fail(HZP_ERR_RANGE, "hzp_gather_layer: no bucket (layer %u, class %u)", layer, cls);
     if (level != 1 && level != 3)
         return fail(HZP_ERR_RANGE, "hzp_gather_layer: level %d is neither 1 nor 3", level);
+    if (level == 1 && plan->K == 0)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layer: z3=%u does not divide z1=%u; use hzp_gather_shard",
+                    plan->z3, plan->z1);
     const uint32_t want = level == 1 ? plan->K : plan->z3;
     if (n_shards != want)
         return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer: level %d takes %u shards, got %u", level, want,
@@ -145,4 +148,39 @@ extern "C" hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer,
     }
     if (tensor_out) return launch_unpack(plan, *b, shard_ptrs, n_shards, tensor_out, stream);
     return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_gather_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, uint32_t j,
+                                         const void *const *owner_ptrs, uint32_t n_owners, void *shard_out,
+                                         hipStream_t stream)
+{
+    if (!plan || !owner_ptrs || !shard_out)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_shard: NULL plan, owner array or output");
+    const BucketRec *b = find_bucket(plan, layer, cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_gather_shard: no bucket (layer %u, class %u)", layer, cls);
+    if (j >= plan->z3) return fail(HZP_ERR_RANGE, "hzp_gather_shard: shard %u of %u", j, plan->z3);
+    const uint64_t lo3 = j * b->S3, hi3 = lo3 + b->S3;
+    const uint64_t first = lo3 / b->S1, want = (hi3 + b->S1 - 1) / b->S1 - first;
+    if (n_owners != want)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_shard: shard %u is covered by %llu ZeRO-1 shards, got %u", j,
+                    (unsigned long long)want, n_owners);
+    if (n_owners > HZP_MAX_GROUP)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_shard: %u owners exceed %u", n_owners, HZP_MAX_GROUP);
+    if (!aligned16(shard_out)) return fail(HZP_ERR_ALIGN, "hzp_gather_shard: shard_out is not 16-byte aligned");
+    const uint32_t es = cls == HZP_CLASS_F32 ? 4u : 2u;
+    const void *src[HZP_MAX_GROUP];
+    uint64_t dst_off[HZP_MAX_GROUP], bytes[HZP_MAX_GROUP];
+    for (uint32_t q = 0; q < n_owners; ++q) {
+        if (!owner_ptrs[q]) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_shard: owner %u is NULL", q);
+        if (!aligned16(owner_ptrs[q]))
+            return fail(HZP_ERR_ALIGN, "hzp_gather_shard: owner %u is not 16-byte aligned", q);
+        // [lo, hi) = the part of ZeRO-1 shard first+q inside shard j; S1, S3 are multiples of A >= 8
+        // elements, so every offset below is a multiple of 16 bytes
+        const uint64_t lo1 = (first + q) * b->S1;
+        const uint64_t lo = lo1 > lo3 ? lo1 : lo3, hi = lo1 + b->S1 < hi3 ? lo1 + b->S1 : hi3;
+        src[q] = static_cast<const char *>(owner_ptrs[q]) + (lo - lo1) * es;
+        dst_off[q] = (lo - lo3) * es;
+        bytes[q] = (hi - lo) * es;
+    }
+    return launch_concat_ranges(src, dst_off, bytes, n_owners, shard_out, stream);
 }

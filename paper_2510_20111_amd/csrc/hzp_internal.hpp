@@ -39,7 +39,7 @@ struct BucketRec {
     uint32_t cls;
     uint32_t first_slot;    // first entry of this bucket in the per-bucket-ordered tables
     uint32_t n_tensors;
-    uint64_t payload_end, P, S3, S1, base;
+    uint64_t payload_end, P, S3, S2, S1, base;
     std::vector<uint32_t> tensor_ids;
     std::vector<Piece> pieces;
     uint32_t n_chunks;
@@ -63,7 +63,9 @@ constexpr uint32_t kUnpackChunk = HZP_UNPACK_CHUNK;   // elements one wavefront 
 }  // namespace hzp
 
 struct hzp_plan {
-    uint32_t n_layers, align, z3, z2, z1, K;
+    uint32_t n_layers, align, z3, z2, z1;
+    uint32_t K;                                 // Z1/Z3, or 0 when Z3 does not divide Z1
+    uint32_t world;                             // lcm(Z1, Z2, Z3): ranks are 0 .. world-1
     uint64_t total_padded;
     bool uniform_wd;                            // every multiplier is 1: no table lookups
     std::vector<hzp::TensorRec> tensors;        // by tensor id
@@ -77,6 +79,8 @@ struct hzp_plan {
 
 namespace hzp {
 const BucketRec *find_bucket(const hzp_plan_t *plan, uint32_t layer, uint32_t cls);
+// Index of the shard that `rank` (< plan->world) owns at `level` (1, 2 or 3).
+uint32_t level_index(const hzp_plan_t *plan, int level, uint32_t rank);
 
 // One shard segment (one layer bucket) of a fused update call.
 struct FusedSegment {
@@ -95,6 +99,10 @@ hzp_status_t launch_fused(const hzp_plan_t *plan, bool g32, bool o32, uint32_t R
                           size_t nseg, const hzp_adamw_t &hy, hipStream_t stream);
 hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t bytes_per_shard, void *dst,
                            hipStream_t stream);
+// Copies n pieces of different lengths: piece s goes from srcs[s] to dst + dst_off[s] (bytes, all
+// multiples of 16).
+hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_off, const uint64_t *bytes,
+                                  uint32_t n, void *dst, hipStream_t stream);
 hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const void *const *shards,
                            uint32_t n_shards, void *const *tensors, hipStream_t stream);
 // Tables for the current device (creates them on first use).  Defined with the launchers.

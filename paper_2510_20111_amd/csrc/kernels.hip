@@ -448,6 +448,30 @@ __global__ __launch_bounds__(kWave) void concat_kernel(const ConcatArgs a)
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(val) : "memory");
 }
 
+// The same copy for pieces of different lengths (a ZeRO-3 shard rebuilt from whole and partial
+// ZeRO-1 shards when the group sizes do not nest).  One-dimensional grid over the 64-vector tiles
+// of all pieces; a workgroup finds its piece by scanning the tile prefix (at most HZP_MAX_GROUP
+// uniform compares), so no workgroup is launched for nothing.
+struct ConcatRangesArgs {
+    const void *src[HZP_MAX_GROUP];         // first vector to read of each piece
+    uint32_t dst_vec[HZP_MAX_GROUP];        // where it goes, in 16-byte vectors from dst
+    uint32_t nvec[HZP_MAX_GROUP];
+    uint32_t tile_end[HZP_MAX_GROUP];       // running count of tiles up to and including the piece
+    u32x4 *dst;
+    uint32_t n;
+};
+__global__ __launch_bounds__(kWave) void concat_ranges_kernel(const ConcatRangesArgs a)
+{
+    uint32_t s = 0;
+    while (s + 1 < a.n && blockIdx.x >= a.tile_end[s]) ++s;
+    const uint32_t tile = blockIdx.x - (s ? a.tile_end[s - 1] : 0u);
+    const uint32_t vec = tile * kWave + threadIdx.x;
+    if (vec >= a.nvec[s]) return;
+    const u32x4 val = ld_stream(reinterpret_cast<const u32x4 *>(a.src[s]) + vec);
+    u32x4 *dst = a.dst + (size_t)a.dst_vec[s] + vec;
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(val) : "memory");
+}
+
 // ---------------------------------------------------------------------------------------
 // Gather + unpack: ZeRO-3 shards -> separate, unpadded tensor buffers.
 // One single-wavefront workgroup per chunk of at most kUnpackChunk elements of one piece (a run of
@@ -713,6 +737,33 @@ hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t 
     const dim3 grid((uint32_t)((nvec + kWave - 1) / kWave), n_shards), block(kWave);
     hipLaunchKernelGGL(concat_kernel, grid, block, 0, stream, a);
     return check_launch("hzp_gather_layer");
+}
+
+hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_off, const uint64_t *bytes,
+                                  uint32_t n, void *dst, hipStream_t stream)
+{
+    ConcatRangesArgs a{};
+    uint64_t tiles = 0, total = 0;
+    bool uniform = true;
+    for (uint32_t s = 0; s < n; ++s) {
+        if (bytes[s] / 16 > 0xFFFFFFFFull || dst_off[s] / 16 > 0xFFFFFFFFull)
+            return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_shard: shard larger than 64 GiB");
+        a.src[s] = srcs[s];
+        a.dst_vec[s] = (uint32_t)(dst_off[s] / 16);
+        a.nvec[s] = (uint32_t)(bytes[s] / 16);
+        tiles += (bytes[s] / 16 + kWave - 1) / kWave;
+        a.tile_end[s] = (uint32_t)tiles;           // checked below
+        uniform = uniform && bytes[s] == bytes[0] && dst_off[s] == s * bytes[0];
+        total += bytes[s];
+    }
+    if (total == 0) return HZP_OK;
+    if (uniform) return launch_concat(srcs, n, bytes[0], dst, stream);     // equal whole pieces
+    if (tiles > 0x7FFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_shard: shard too large for one launch");
+    a.dst = reinterpret_cast<u32x4 *>(dst);
+    a.n = n;
+    const dim3 grid((uint32_t)tiles), block(kWave);
+    hipLaunchKernelGGL(concat_ranges_kernel, grid, block, 0, stream, a);
+    return check_launch("hzp_gather_shard");
 }
 
 hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const void *const *shards,

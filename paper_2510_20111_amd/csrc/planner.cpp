@@ -2,11 +2,12 @@
 // Host-only 64-bit integer code; it makes no HIP call, so a plan can be built without a GPU.
 //
 // Group sizes follow the memory model of Section 4.1.1 (M_hzp = 12N/Z1 + 4N/Z2 + 2N/Z3):
-// Z1 shards the optimizer states, Z2 the gradients, Z3 the parameters.  The bucket rule
-// (A-aligned tensor starts, zero padding up to a multiple of A*Z1) and the rank map
-// (j = r mod Z3, k = r div Z3, i = j*K + k) are this library's own choices; the paper only
-// asks that parameters and gradients live in a small group and optimizer states in a larger
-// one (Figure 1, Section 3.1).
+// Z1 shards the optimizer states, Z2 the gradients, Z3 the parameters, each chosen freely.  The
+// bucket rule (A-aligned tensor starts, zero padding up to a multiple of A*lcm(Z1,Z2,Z3)) and the
+// rank map (nested wherever one group size divides the next; with Z2 = Z3 | Z1 it is
+// j = r mod Z3, k = r div Z3, i = j*K + k) are this library's own choices; the paper only asks
+// that parameters and gradients live in a small group and optimizer states in a larger one
+// (Figure 1, Section 3.1).
 #include <cstdarg>
 #include <cstdio>
 #include <new>
@@ -31,6 +32,30 @@ const BucketRec *find_bucket(const hzp_plan_t *plan, uint32_t layer, uint32_t cl
     if (layer >= plan->n_layers || cls > 1) return nullptr;
     int32_t b = plan->bucket_of[layer * 2 + cls];
     return b < 0 ? nullptr : &plan->buckets[b];
+}
+
+uint32_t level_index(const hzp_plan_t *plan, int level, uint32_t rank)
+{
+    const uint32_t z1 = plan->z1, z2 = plan->z2, z3 = plan->z3;
+    const uint32_t j3 = rank % z3;
+    if (level == 3) return j3;
+    const bool up32 = z2 % z3 == 0;
+    const uint32_t j2 = up32 ? j3 * (z2 / z3) + rank / z3 % (z2 / z3) : rank % z2;
+    if (level == 2) return j2;
+    const bool chain = up32 && z1 % z2 == 0;
+    if (z1 % z3 == 0 && !chain) return j3 * (z1 / z3) + rank / z3 % (z1 / z3);
+    if (z1 % z2 == 0) return j2 * (z1 / z2) + rank / z2 % (z1 / z2);
+    return rank % z1;
+}
+
+static uint64_t gcd64(uint64_t a, uint64_t b)
+{
+    while (b) {
+        const uint64_t t = a % b;
+        a = b;
+        b = t;
+    }
+    return a;
 }
 
 static bool round_up(uint64_t x, uint64_t q, uint64_t *out)
@@ -86,10 +111,10 @@ extern "C" hzp_status_t hzp_plan(const hzp_plan_desc_t *d, hzp_plan_t **out)
         return fail(HZP_ERR_INVALID_ARG, "hzp_plan: align_elems=%u must be a power of two >= 8", A);
     if (d->z3 == 0 || d->z1 == 0)
         return fail(HZP_ERR_INVALID_ARG, "hzp_plan: group sizes must be positive");
-    if (d->z1 % d->z3 != 0)
-        return fail(HZP_ERR_UNSUPPORTED, "hzp_plan: z3=%u must divide z1=%u", d->z3, d->z1);
-    if (d->z2 != 0 && d->z2 != d->z3)
-        return fail(HZP_ERR_UNSUPPORTED, "hzp_plan: z2=%u must be 0 or equal to z3=%u", d->z2, d->z3);
+    const uint32_t z2 = d->z2 ? d->z2 : d->z3;
+    uint64_t world = (uint64_t)d->z1 / gcd64(d->z1, z2) * z2;          // < 2^64: both factors < 2^32
+    if (world > 0xFFFFFFFFull || (world = world / gcd64(world, d->z3) * d->z3) > 0xFFFFFFFFull)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_plan: lcm(z1=%u, z2=%u, z3=%u) exceeds 32 bits", d->z1, z2, d->z3);
     uint64_t n_tensors = 0;
     for (uint32_t l = 0; l < d->n_layers; ++l) {
         if (d->tensors_per_layer[l] == 0)
@@ -111,13 +136,14 @@ extern "C" hzp_status_t hzp_plan(const hzp_plan_desc_t *d, hzp_plan_t **out)
         p->n_layers = d->n_layers;
         p->align = A;
         p->z3 = d->z3;
-        p->z2 = d->z3;
+        p->z2 = z2;
         p->z1 = d->z1;
-        p->K = d->z1 / d->z3;
+        p->K = d->z1 % d->z3 == 0 ? d->z1 / d->z3 : 0;
+        p->world = (uint32_t)world;
         p->uniform_wd = true;
         p->tensors.resize(n_tensors);
         p->bucket_of.assign((size_t)d->n_layers * 2, -1);
-        const uint64_t quantum = (uint64_t)A * d->z1;
+        const uint64_t quantum = (uint64_t)A * world;     // every level's shard is a multiple of A
         uint64_t base = 0;
         uint32_t tid0 = 0, slot = 0, piece_slot = 0;
         for (uint32_t l = 0; l < d->n_layers; ++l) {
@@ -156,6 +182,7 @@ extern "C" hzp_status_t hzp_plan(const hzp_plan_desc_t *d, hzp_plan_t **out)
                 }
                 b.base = base - b.P;
                 b.S3 = b.P / d->z3;
+                b.S2 = b.P / z2;
                 b.S1 = b.P / d->z1;
                 b.piece_slot = piece_slot;
                 if (!build_pieces(p, b)) {
@@ -200,6 +227,7 @@ extern "C" hzp_status_t hzp_plan_info(const hzp_plan_t *plan, hzp_plan_info_t *o
     o->z2 = plan->z2;
     o->z1 = plan->z1;
     o->k = plan->K;
+    o->world = plan->world;
     o->total_padded = plan->total_padded;
     return HZP_OK;
 }
@@ -219,6 +247,7 @@ extern "C" hzp_status_t hzp_plan_bucket(const hzp_plan_t *plan, uint32_t layer, 
     o->s3 = b->S3;
     o->s1 = b->S1;
     o->base = b->base;
+    o->s2 = b->S2;
     return HZP_OK;
 }
 
@@ -242,11 +271,20 @@ extern "C" hzp_status_t hzp_plan_rank(const hzp_plan_t *plan, uint32_t rank, uin
                                       uint32_t *i)
 {
     if (!plan) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_rank: NULL plan");
-    if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_plan_rank: rank %u of %u", rank, plan->z1);
-    const uint32_t jj = rank % plan->z3, kk = rank / plan->z3;
+    if (rank >= plan->world) return fail(HZP_ERR_RANGE, "hzp_plan_rank: rank %u of %u", rank, plan->world);
+    const uint32_t jj = level_index(plan, 3, rank), ii = level_index(plan, 1, rank);
     if (j) *j = jj;
-    if (k) *k = kk;
-    if (i) *i = jj * plan->K + kk;
+    if (k) *k = plan->K ? ii - jj * plan->K : 0;
+    if (i) *i = ii;
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_plan_index(const hzp_plan_t *plan, int level, uint32_t rank, uint32_t *index)
+{
+    if (!plan || !index) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_index: NULL argument");
+    if (level < 1 || level > 3) return fail(HZP_ERR_RANGE, "hzp_plan_index: level %d is not 1, 2 or 3", level);
+    if (rank >= plan->world) return fail(HZP_ERR_RANGE, "hzp_plan_index: rank %u of %u", rank, plan->world);
+    *index = level_index(plan, level, rank);
     return HZP_OK;
 }
 
@@ -256,17 +294,24 @@ extern "C" hzp_status_t hzp_plan_shard(const hzp_plan_t *plan, uint32_t layer, u
     if (!plan || !begin || !len) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_shard: NULL argument");
     const BucketRec *b = find_bucket(plan, layer, cls);
     if (!b) return fail(HZP_ERR_RANGE, "hzp_plan_shard: no bucket (layer %u, class %u)", layer, cls);
-    if (rank >= plan->z1) return fail(HZP_ERR_RANGE, "hzp_plan_shard: rank %u of %u", rank, plan->z1);
-    const uint64_t j = rank % plan->z3, k = rank / plan->z3;
-    if (level == 3) {
-        *begin = j * b->S3;
-        *len = b->S3;
-    } else if (level == 1) {
-        *begin = (j * plan->K + k) * b->S1;
-        *len = b->S1;
-    } else {
-        return fail(HZP_ERR_RANGE, "hzp_plan_shard: level %d is neither 1 nor 3", level);
-    }
+    if (rank >= plan->world) return fail(HZP_ERR_RANGE, "hzp_plan_shard: rank %u of %u", rank, plan->world);
+    if (level < 1 || level > 3) return fail(HZP_ERR_RANGE, "hzp_plan_shard: level %d is not 1, 2 or 3", level);
+    const uint64_t s = level == 1 ? b->S1 : level == 2 ? b->S2 : b->S3;
+    *begin = level_index(plan, level, rank) * s;
+    *len = s;
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_plan_cover(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, uint32_t j,
+                                       uint32_t *first_owner, uint32_t *n_owners)
+{
+    if (!plan || !first_owner || !n_owners) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_cover: NULL argument");
+    const BucketRec *b = find_bucket(plan, layer, cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_plan_cover: no bucket (layer %u, class %u)", layer, cls);
+    if (j >= plan->z3) return fail(HZP_ERR_RANGE, "hzp_plan_cover: shard %u of %u", j, plan->z3);
+    const uint64_t lo = j * b->S3, hi = lo + b->S3;             // S1, S3 >= A > 0
+    *first_owner = (uint32_t)(lo / b->S1);
+    *n_owners = (uint32_t)((hi + b->S1 - 1) / b->S1 - lo / b->S1);
     return HZP_OK;
 }
 
@@ -307,4 +352,33 @@ extern "C" hzp_status_t hzp_memory_model(uint64_t n, uint32_t z1, uint32_t z2, u
     if (q >> 64) return fail(HZP_ERR_UNSUPPORTED, "hzp_memory_model: result exceeds 64 bits");
     *bytes = (uint64_t)q;
     return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_choose_groups(uint64_t n, uint32_t dp, uint32_t node, uint64_t budget,
+                                          uint32_t *z1, uint32_t *z2, uint32_t *z3)
+{
+    if (!z1 || !z2 || !z3) return fail(HZP_ERR_INVALID_ARG, "hzp_choose_groups: NULL output");
+    if (dp == 0 || node == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_choose_groups: dp and node must be positive");
+    if (dp > (1u << 20)) return fail(HZP_ERR_UNSUPPORTED, "hzp_choose_groups: dp=%u exceeds 2^20", dp);
+    uint32_t last3 = 1, last1 = 1;
+    for (uint32_t c3 = 1; c3 <= node && c3 <= dp; ++c3) {       // ascending Z3, then ascending Z1
+        if (node % c3 || dp % c3) continue;
+        for (uint64_t c1 = c3; c1 <= dp; c1 += c3) {
+            if (dp % c1) continue;
+            uint64_t bytes;
+            const hzp_status_t st = hzp_memory_model(n, (uint32_t)c1, c3, c3, &bytes);
+            if (st != HZP_OK) return st;
+            last3 = c3;
+            last1 = (uint32_t)c1;
+            if (bytes <= budget) {          // ceil(M) <= budget  <=>  M <= budget for an integer budget
+                *z1 = (uint32_t)c1;
+                *z2 = *z3 = c3;
+                return HZP_OK;
+            }
+        }
+    }
+    *z1 = last1;
+    *z2 = *z3 = last3;
+    return fail(HZP_ERR_NOMEM, "hzp_choose_groups: even Z1=%u, Z2=Z3=%u exceeds %llu bytes", last1, last3,
+                (unsigned long long)budget);
 }

@@ -108,8 +108,8 @@ def wd_mult_array(oplan, bucket, begin, n):
     return out
 
 
-def oracle_plan(desc, align, z3, z1):
-    return op.make_plan(desc["tensors_per_layer"], desc["tensor_numel"], align, z3, z1,
+def oracle_plan(desc, align, z3, z1, z2=0):
+    return op.make_plan(desc["tensors_per_layer"], desc["tensor_numel"], align, z3, z1, z2,
                         tensor_class=desc.get("tensor_class"),
                         tensor_wd_mult=desc.get("tensor_wd_mult"))
 

@@ -49,8 +49,8 @@ FAKE = 0x10000      # a non-null, 16-byte aligned address that is never derefere
     (dict(align=12), hzp.HZP_ERR_INVALID_ARG),
     (dict(align=4), hzp.HZP_ERR_INVALID_ARG),
     (dict(z3=0), hzp.HZP_ERR_INVALID_ARG),
-    (dict(z3=3, z1=8), hzp.HZP_ERR_UNSUPPORTED),
-    (dict(z2=4), hzp.HZP_ERR_UNSUPPORTED),
+    (dict(z1=0), hzp.HZP_ERR_INVALID_ARG),
+    (dict(z3=65537, z1=65536, z2=65539), hzp.HZP_ERR_UNSUPPORTED),      # lcm exceeds 32 bits
     (dict(tensor_numel=[0, 5]), hzp.HZP_ERR_INVALID_ARG),
     (dict(tensors_per_layer=[0, 2]), hzp.HZP_ERR_INVALID_ARG),
     (dict(tensor_class=[0, 2]), hzp.HZP_ERR_INVALID_ARG),
@@ -68,8 +68,13 @@ def test_plan_query_errors():
     assert _status(p.bucket, 1, 1) == hzp.HZP_ERR_RANGE          # layer 1 has no fp32 tensor
     assert _status(p.tensor, 3) == hzp.HZP_ERR_RANGE
     assert _status(p.rank, 4) == hzp.HZP_ERR_RANGE
-    assert _status(p.shard, 0, 0, 2, 0) == hzp.HZP_ERR_RANGE
+    assert _status(p.shard, 0, 0, 0, 0) == hzp.HZP_ERR_RANGE
+    assert _status(p.shard, 0, 0, 4, 0) == hzp.HZP_ERR_RANGE
     assert _status(p.shard, 0, 0, 1, 4) == hzp.HZP_ERR_RANGE
+    assert _status(p.index, 4, 0) == hzp.HZP_ERR_RANGE
+    assert _status(p.index, 1, 4) == hzp.HZP_ERR_RANGE
+    assert _status(p.cover, 0, 0, 2) == hzp.HZP_ERR_RANGE
+    assert _status(p.cover, 1, 1, 0) == hzp.HZP_ERR_RANGE
 
 
 def test_reduce_argument_errors():
@@ -82,7 +87,8 @@ def test_reduce_argument_errors():
     assert _status(f, p, 0, 0, 1, 0, [FAKE], 1.0, 0, FAKE + 4, stream=0) == hzp.HZP_ERR_ALIGN
     assert _status(f, p, 0, 0, 1, 0, [FAKE], 1.0, 0, 0, stream=0) == hzp.HZP_ERR_INVALID_ARG
     assert _status(f, p, 5, 0, 1, 0, [FAKE], 1.0, 0, FAKE, stream=0) == hzp.HZP_ERR_RANGE
-    assert _status(f, p, 0, 0, 2, 0, [FAKE], 1.0, 0, FAKE, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 0, 0, 0, 0, [FAKE], 1.0, 0, FAKE, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 0, 0, 4, 0, [FAKE], 1.0, 0, FAKE, stream=0) == hzp.HZP_ERR_RANGE
     assert _status(f, p, 0, 0, 1, 9, [FAKE], 1.0, 0, FAKE, stream=0) == hzp.HZP_ERR_RANGE
 
 
@@ -119,6 +125,25 @@ def test_gather_argument_errors():
     assert _status(f, p, 1, 1, 3, [FAKE] * 2, FAKE, None, stream=0) == hzp.HZP_ERR_RANGE
     big = hzp.hzp_plan([1], [8 * 128], align=8, z3=128, z1=128)
     assert _status(f, big, 0, 0, 3, [FAKE] * 128, FAKE, None, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+    loose = hzp.hzp_plan([1], [100], align=8, z3=4, z1=6, z2=2)      # Z3 does not divide Z1
+    assert _status(f, loose, 0, 0, 1, [FAKE] * 2, FAKE, None, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+
+
+def test_gather_shard_argument_errors():
+    p = hzp.hzp_plan([1], [100], align=8, z3=4, z1=6, z2=2)          # S1 = 32, S3 = 48: two owners per shard
+    f = hzp.hzp_gather_shard
+    assert p.cover(0, 0, 1) == (1, 2)
+    assert _status(f, p, 0, 0, 1, [FAKE], FAKE, stream=0) == hzp.HZP_ERR_INVALID_ARG            # cover has 2
+    assert _status(f, p, 0, 0, 1, [FAKE] * 3, FAKE, stream=0) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(f, p, 0, 0, 4, [FAKE] * 2, FAKE, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 1, 0, 0, [FAKE] * 2, FAKE, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 0, 1, 0, [FAKE] * 2, FAKE, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 0, 0, 1, [FAKE, 0], FAKE, stream=0) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(f, p, 0, 0, 1, [FAKE, FAKE + 4], FAKE, stream=0) == hzp.HZP_ERR_ALIGN
+    assert _status(f, p, 0, 0, 1, [FAKE] * 2, FAKE + 8, stream=0) == hzp.HZP_ERR_ALIGN
+    assert _status(f, p, 0, 0, 1, [FAKE] * 2, 0, stream=0) == hzp.HZP_ERR_INVALID_ARG
+    wide = hzp.hzp_plan([1], [8], align=8, z3=1, z1=65)              # 65 owners for the one shard
+    assert _status(f, wide, 0, 0, 0, [FAKE] * 65, FAKE, stream=0) == hzp.HZP_ERR_UNSUPPORTED
 
 
 def test_scheduler_argument_errors_before_any_gpu_call():

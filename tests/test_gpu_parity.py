@@ -18,8 +18,8 @@ pytestmark = pytest.mark.gpu
 HP = hzp_inputs.ADAMW
 
 
-def lib_plan(desc, align, z3, z1):
-    return hzp.hzp_plan(desc["tensors_per_layer"], desc["tensor_numel"], align, z3, z1,
+def lib_plan(desc, align, z3, z1, z2=0):
+    return hzp.hzp_plan(desc["tensors_per_layer"], desc["tensor_numel"], align, z3, z1, z2,
                         tensor_class=desc.get("tensor_class"),
                         tensor_wd_mult=desc.get("tensor_wd_mult"))
 
@@ -99,9 +99,9 @@ def test_reduce_order_pin_on_gpu():
 class Sim:
     """State of all ranks of one plan on both sides: oracle (numpy) and library (device)."""
 
-    def __init__(self, desc, align, z3, z1, R, sigma, seed, ranks=None):
+    def __init__(self, desc, align, z3, z1, R, sigma, seed, ranks=None, z2=0):
         self.desc, self.R, self.sigma, self.seed = desc, R, sigma, seed
-        self.oplan, self.plan = oracle_plan(desc, align, z3, z1), lib_plan(desc, align, z3, z1)
+        self.oplan, self.plan = oracle_plan(desc, align, z3, z1, z2), lib_plan(desc, align, z3, z1, z2)
         self.ranks = list(range(z1)) if ranks is None else ranks
         self.o = {}     # (bucket index, rank) -> dict p, m, v, out (numpy)
         self.d = {}     # same on the device, with guard bands

@@ -7,15 +7,15 @@ from oracle import planner as op
 
 
 def _compare(d):
-    want = op.make_plan(d["tensors_per_layer"], d["tensor_numel"], d["align"], d["z3"], d["z1"],
+    want = op.make_plan(d["tensors_per_layer"], d["tensor_numel"], d["align"], d["z3"], d["z1"], d.get("z2", 0),
                         tensor_class=d.get("tensor_class"), tensor_wd_mult=d.get("tensor_wd_mult"))
-    got = hzp.hzp_plan(d["tensors_per_layer"], d["tensor_numel"], d["align"], d["z3"], d["z1"],
+    got = hzp.hzp_plan(d["tensors_per_layer"], d["tensor_numel"], d["align"], d["z3"], d["z1"], d.get("z2", 0),
                        tensor_class=d.get("tensor_class"), tensor_wd_mult=d.get("tensor_wd_mult"))
     info = got.info()
     assert (info.n_layers, info.n_buckets, info.n_tensors) == (
         want["n_layers"], len(want["buckets"]), len(want["tensors"]))
-    assert (info.align_elems, info.z3, info.z2, info.z1, info.k, info.total_padded) == (
-        want["align"], want["z3"], want["z2"], want["z1"], want["K"], want["total_padded"])
+    assert (info.align_elems, info.z3, info.z2, info.z1, info.k, info.world, info.total_padded) == (
+        want["align"], want["z3"], want["z2"], want["z1"], want["K"], want["world"], want["total_padded"])
     for layer in range(want["n_layers"]):
         for cls in (0, 1):
             wb = op.find_bucket(want, layer, cls)
@@ -23,16 +23,25 @@ def _compare(d):
     for idx, wb in enumerate(want["buckets"]):
         gb = got.bucket(wb["layer"], wb["cls"])
         assert (gb.layer, gb.cls, gb.n_tensors, gb.bucket_index, gb.payload_end, gb.padded, gb.s3,
-                gb.s1, gb.base) == (wb["layer"], wb["cls"], len(wb["tensor_ids"]), idx,
-                                    wb["payload_end"], wb["P"], wb["S3"], wb["S1"], wb["base"])
-        ranks = range(want["z1"]) if want["z1"] <= 16 else [0, 1, want["z3"], want["z1"] - 1]
+                gb.s2, gb.s1, gb.base) == (wb["layer"], wb["cls"], len(wb["tensor_ids"]), idx,
+                                           wb["payload_end"], wb["P"], wb["S3"], wb["S2"], wb["S1"], wb["base"])
+        W = want["world"]
+        ranks = range(W) if W <= 16 else [0, 1, want["z3"], want["z1"] - 1, W - 1]
         for rank in ranks:
-            for level in (1, 3):
+            for level in (1, 2, 3):
                 assert got.shard(wb["layer"], wb["cls"], level, rank) == \
                     op.shard_range(want, wb, level, rank)
-    ranks = range(want["z1"]) if want["z1"] <= 64 else [0, 1, 7, 8, want["z1"] - 1]
+        shards3 = range(want["z3"]) if want["z3"] <= 16 else [0, 1, want["z3"] - 1]
+        for j in shards3:
+            cover = op.cover(want, wb, j)
+            assert got.cover(wb["layer"], wb["cls"], j) == (cover[0][0], len(cover))
+            assert [c[0] for c in cover] == list(range(cover[0][0], cover[0][0] + len(cover)))
+    W = want["world"]
+    ranks = range(W) if W <= 64 else [0, 1, 7, 8, want["z1"] - 1, W - 1]
     for rank in ranks:
         assert got.rank(rank) == op.rank_to_indices(want, rank)
+        for level in (1, 2, 3):
+            assert got.index(level, rank) == op.level_index(want, level, rank)
     tensor_ids = range(len(want["tensors"])) if len(want["tensors"]) <= 300 else \
         list(range(0, len(want["tensors"]), 37)) + [len(want["tensors"]) - 1]
     for t in tensor_ids:
@@ -62,6 +71,20 @@ def descriptors(draw):
 @given(descriptors())
 def test_random_descriptors(d):
     _compare(d)
+
+
+@settings(max_examples=150, deadline=None)
+@given(descriptors(), st.integers(1, 12), st.integers(1, 12), st.integers(1, 12))
+def test_random_descriptors_with_free_group_sizes(d, z1, z2, z3):
+    _compare(dict(d, z1=z1, z2=z2, z3=z3))
+
+
+def test_group_sizes_whose_lcm_exceeds_32_bits_are_refused():
+    import pytest
+    with pytest.raises(hzp.HzpError) as e:
+        hzp.hzp_plan([1], [8], 8, 65537, 65536, 65539)
+    assert e.value.status == hzp.HZP_ERR_UNSUPPORTED
+    hzp.hzp_plan([1], [8], 8, 1 << 20, 1 << 30, 1 << 10)         # lcm = 2^30 is fine
 
 
 def test_the_five_workloads():
@@ -100,3 +123,30 @@ def test_memory_model_matches_closed_form():
         hzp.hzp_memory_model(5, 0, 1, 1)
     with pytest.raises(hzp.HzpError):
         hzp.hzp_memory_model(2 ** 63, 1, 1, 1)
+
+
+def test_choose_groups_matches_the_oracle():
+    import os
+    import pytest
+    golden = os.path.join(os.path.dirname(__file__), "golden", "choose_groups.txt")
+    cases = []
+    with open(golden) as f:
+        for line in f:
+            row = line.split("#")[0].split()
+            if row:
+                cases.append(tuple(int(x) for x in row[:4]))
+    cases += [(12345, 48, 8, b) for b in range(0, 230000, 7919)]
+    cases += [(10 ** 12, 4096, 8, b * 10 ** 9) for b in (1, 50, 800, 1600, 20000)]
+    cases += [(999, 36, 6, b) for b in range(500, 19000, 613)] + [(0, 8, 8, 0), (5, 1, 8, 90), (5, 1, 8, 89)]
+    for N, dp, node, budget in cases:
+        want = op.choose_groups(N, dp, node, budget)
+        if want is None:
+            with pytest.raises(hzp.HzpError) as e:
+                hzp.hzp_choose_groups(N, dp, node, budget)
+            assert e.value.status == hzp.HZP_ERR_NOMEM
+        else:
+            assert hzp.hzp_choose_groups(N, dp, node, budget) == want, (N, dp, node, budget)
+    for bad in [(5, 0, 8, 1), (5, 8, 0, 1)]:
+        with pytest.raises(hzp.HzpError) as e:
+            hzp.hzp_choose_groups(*bad)
+        assert e.value.status == hzp.HZP_ERR_INVALID_ARG
