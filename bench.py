@@ -329,8 +329,8 @@ def run_step(w, hzp, step, stream, phases, events=None):
 
 
 def copy_probe(torch, hzp, stream):
-    """Achievable-bandwidth context: the library's own concat kernel used as a plain copy
-    (Z3 = 1) on 1 GiB, and torch's device-to-device copy of the same buffers."""
+    """Achievable-bandwidth context: a copy and a triad of 1 GiB arrays, each with the library's
+    own kernel (concat with Z3 = 1; reduction of two fp32 contributions) and with torch."""
     n = 1 << 29     # bf16 elements = 1 GiB
     plan = hzp.hzp_plan([1], [n], 8, 1, 1)
     src = torch.empty(n, dtype=torch.bfloat16, device="cuda:0").normal_()
@@ -349,6 +349,29 @@ def copy_probe(torch, hzp, stream):
             e1.record(stream)
         stream.synchronize()
         out[name + "_GBps"] = round(2 * n * 2 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    del src, dst
+    # triad (two reads, one write per element: the read/write mix of the fused update): the
+    # library's reduction of two fp32 contributions, a = s*(b + c), and torch's a = b + s*c
+    nt = 1 << 28     # fp32 elements = 1 GiB per array
+    plan_t = hzp.hzp_plan([1], [nt], 8, 1, 1)
+    b = torch.empty(nt, dtype=torch.float32, device="cuda:0").normal_()
+    c = torch.empty_like(b).normal_()
+    a = torch.empty_like(b)
+    bc = hzp.ptr_array([b, c])
+    for name, fn in (("hzp_reduce_triad", lambda: hzp.hzp_reduce_shard(plan_t, 0, 0, 1, 0, bc, 0.5, False, a,
+                                                                        stream=stream.cuda_stream, R=2,
+                                                                        grad_dtype=hzp.HZP_GRAD_F32)),
+                     ("torch_triad", lambda: torch.add(b, c, alpha=0.5, out=a))):
+        with torch.cuda.stream(stream):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                fn()
+            e1.record(stream)
+        stream.synchronize()
+        out[name + "_GBps"] = round(3 * nt * 4 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
     return out
 
 
