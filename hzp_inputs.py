@@ -33,7 +33,7 @@ def _dense_layer(hidden, ffn, q_out=None, kv_out=None):
 
 
 def config(idx):
-    """Workload `idx` (0..4) as plain lists: the order follows BASELINE's configs."""
+    """Workload `idx` (0..4) as plain lists: tiny, dense7b, dense70b, moe, irregular."""
     if idx == 0:      # tiny 2-layer transformer state, 16 tensors
         layers = [("embed", ["tok_embed", "final_norm"], [1024 * 256, 256])]
         for l in range(2):
