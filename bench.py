@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
-                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,perlayer,freegroups,overlap")
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,prereduced,perlayer,freegroups,overlap")
     return ap.parse_args()
 
 
@@ -152,6 +152,11 @@ def add_secondary_buffers(w, phases):
                       for r in range(w.R)]
             acc = w._piece("acc", w.s3_total, torch.float32, o3, b.s3).zero_()
             w.accum_args.append((l, hzp.ptr_array(slices), acc, slices))
+    if "prereduced" in phases and getattr(w, "pre_arr", None) is None:
+        # the update from an already reduced fp32 gradient shard (R == 0 form): 30 B per parameter
+        w.pre_keep = [w._piece("gpre", w.s1_total, torch.float32, b.base // w.cfg["z1"], b.s1).normal_(0.0, w.cfg["sigma"])
+                      for b in w.buckets]
+        w.pre_arr = hzp.ptr_array(w.pre_keep)
     if "freegroups" in phases and getattr(w, "free_args", None) is None:
         # the same layers under group sizes that do not nest (Z1 = 3*Z3/2): ZeRO-3 shard 1 of every
         # layer is rebuilt from one partial and one whole ZeRO-1 shard
@@ -186,6 +191,11 @@ def run_secondary(w, hzp, stream, phase):
         hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], w.cfg["grad_scale"], 1)
         for l, g, p, m, v, o in w.layer_args:
             hzp.hzp_adamw_shard(w.plan, l, l + 1, 0, w.rank, hy, g, w.R, p, m, v, o, stream=s)
+    elif phase == "prereduced":
+        a = w.cfg["adamw"]
+        hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], 1.0, 1)
+        hzp.hzp_adamw_shard(w.plan, 0, w.n_layers, 0, w.rank, hy, w.pre_arr, 0, w.p_arr, w.m_arr, w.v_arr, w.o_arr,
+                            stream=s)
     elif phase == "freegroups":
         for l, owners, dst, _ in w.free_args:
             hzp.hzp_gather_shard(w.free_plan, l, 0, 1, owners, dst, stream=s)
@@ -525,13 +535,16 @@ def main():
             ms = time_secondary(w, hzp, torch, stream, phase, args.steps, args.warmup)
             nbytes = {"unpack": lambda: 4 * w.payload_total, "reduce": lambda: (2 * R + 4) * w.s3_total,
                       "accumulate": lambda: (4 * R + 8) * w.s3_total,
-                      "perlayer": lambda: fused_bytes, "freegroups": lambda: 4 * w.free_s3_total}[phase]()
+                      "perlayer": lambda: fused_bytes, "freegroups": lambda: 4 * w.free_s3_total,
+                      "prereduced": lambda: 30 * w.s1_total}[phase]()
             kname = {"unpack": "unpack_kernel<2>", "reduce": "reduce_kernel<bf16,R=%d>" % R,
                      "accumulate": "reduce_kernel<f32,R=%d,accumulate>" % R,
                      "perlayer": "fused_adamw_kernel<R=%d,bf16>, one call per layer" % R,
+                     "prereduced": "fused_adamw_kernel<R=1,f32 gradient> (update from a reduced fp32 shard)",
                      "freegroups": "concat_ranges_kernel (Z1=%d over Z3=%d: ZeRO-3 shard from partial owners)"
                                    % (getattr(w, "free_z1", 0), w.z3)}[phase]
-            result["secondary"][phase] = roof(kname, nbytes, ms, w.n_layers, "%s_%s" % (phase, cfg["name"]))
+            launches = fused_launches if phase == "prereduced" else w.n_layers
+            result["secondary"][phase] = roof(kname, nbytes, ms, launches, "%s_%s" % (phase, cfg["name"]))
             result["secondary"][phase].pop("share_of_step_time")
     if not args.no_probe:
         result["hbm_probe"] = copy_probe(torch, hzp, stream)
