@@ -275,6 +275,23 @@ hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer, uint32_t c
                               void *const *tensor_out, hipStream_t stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Gather of one parameter: the all-gather at parameter granularity that Section 4.2 prefers to
+ * whole buckets.  Rebuilds tensor `tensor_id` (numbering of hzp_plan_tensor) from the ZeRO-3 shards
+ * of its bucket:
+ *
+ *     tensor_out[y] = shard_ptrs[j][(offset + y) - j*S3],   j = (offset + y) div S3,   y < numel
+ *
+ *   shard_ptrs : host array [Z3] of device pointers to the bucket's WHOLE ZeRO-3 shards, 16-byte
+ *                aligned; only the shards that hold a part of the tensor are read, the other
+ *                entries may be NULL
+ *   tensor_out : device pointer to numel elements of the tensor's class, element-aligned only
+ * Bit copy.  Errors: INVALID_ARG (NULL, n_shards != Z3, a needed shard is NULL), RANGE (tensor_id),
+ * UNSUPPORTED (more than HZP_MAX_GROUP shards), ALIGN, NOMEM, HIP.
+ * ------------------------------------------------------------------------------------------ */
+hzp_status_t hzp_gather_tensor(const hzp_plan_t *plan, uint32_t tensor_id, const void *const *shard_ptrs,
+                               uint32_t n_shards, void *tensor_out, hipStream_t stream);
+
+/* ------------------------------------------------------------------------------------------
  * Post-step parameter gather for free group sizes (Section 4.1.1: the three sizes are independent;
  * Section 4.1.2 "Optimizer Step": updated parameters are gathered back into the parameter shards).
  * Rebuilds ZeRO-3 shard j of bucket (layer, cls) from the ZeRO-1 shards that meet it:

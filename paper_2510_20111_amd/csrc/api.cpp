@@ -146,7 +146,7 @@ extern "C" hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer,
         hzp_status_t st = launch_concat(shard_ptrs, n_shards, len * es, bucket_out, stream);
         if (st != HZP_OK) return st;
     }
-    if (tensor_out) return launch_unpack(plan, *b, shard_ptrs, n_shards, tensor_out, stream);
+    if (tensor_out) return launch_unpack(plan, *b, shard_ptrs, n_shards, tensor_out, 0, b->n_tensors, stream);
     return HZP_OK;
 }
 
@@ -183,4 +183,34 @@ extern "C" hzp_status_t hzp_gather_shard(const hzp_plan_t *plan, uint32_t layer,
         bytes[q] = (hi - lo) * es;
     }
     return launch_concat_ranges(src, dst_off, bytes, n_owners, shard_out, stream);
+}
+
+extern "C" hzp_status_t hzp_gather_tensor(const hzp_plan_t *plan, uint32_t tensor_id,
+                                          const void *const *shard_ptrs, uint32_t n_shards, void *tensor_out,
+                                          hipStream_t stream)
+{
+    if (!plan || !shard_ptrs || !tensor_out)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_tensor: NULL plan, shard array or output");
+    if (tensor_id >= plan->tensors.size())
+        return fail(HZP_ERR_RANGE, "hzp_gather_tensor: tensor %u of %zu", tensor_id, plan->tensors.size());
+    const TensorRec &t = plan->tensors[tensor_id];
+    const BucketRec &b = plan->buckets[t.bucket];
+    if (n_shards != plan->z3)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_tensor: takes %u shards, got %u", plan->z3, n_shards);
+    if (n_shards > HZP_MAX_GROUP)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_tensor: %u shards exceed %u", n_shards, HZP_MAX_GROUP);
+    const uint32_t es = t.cls == HZP_CLASS_F32 ? 4u : 2u;
+    if (reinterpret_cast<uintptr_t>(tensor_out) % es)
+        return fail(HZP_ERR_ALIGN, "hzp_gather_tensor: tensor_out is not element-aligned");
+    // Only the shards that hold a part of the tensor are read; the other entries are not touched.
+    const uint64_t j0 = t.offset / b.S3, j1 = (t.offset + t.numel - 1) / b.S3;
+    const void *sh[HZP_MAX_GROUP] = {};
+    for (uint64_t j = j0; j <= j1; ++j) {
+        if (!shard_ptrs[j]) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_tensor: shard %llu is NULL", (unsigned long long)j);
+        if (!aligned16(shard_ptrs[j]))
+            return fail(HZP_ERR_ALIGN, "hzp_gather_tensor: shard %llu is not 16-byte aligned", (unsigned long long)j);
+        sh[j] = shard_ptrs[j];
+    }
+    void *out[1] = {tensor_out};
+    return launch_unpack(plan, b, sh, n_shards, out, t.index_in_bucket, t.index_in_bucket + 1, stream);
 }

@@ -103,8 +103,10 @@ hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t 
 // multiples of 16).
 hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_off, const uint64_t *bytes,
                                   uint32_t n, void *dst, hipStream_t stream);
+// Unpacks tensors [t_begin, t_end) of the bucket (indices in the bucket); tensors[0] is t_begin's.
 hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const void *const *shards,
-                           uint32_t n_shards, void *const *tensors, hipStream_t stream);
+                           uint32_t n_shards, void *const *tensors, uint32_t t_begin, uint32_t t_end,
+                           hipStream_t stream);
 // Tables for the current device (creates them on first use).  Defined with the launchers.
 hzp_status_t device_tables(const hzp_plan_t *plan, const DeviceTables **out);
 void free_device_tables(hzp_plan_t *plan);

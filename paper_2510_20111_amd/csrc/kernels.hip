@@ -767,20 +767,22 @@ hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_o
 }
 
 hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const void *const *shards,
-                           uint32_t n_shards, void *const *tensors, hipStream_t stream)
+                           uint32_t n_shards, void *const *tensors, uint32_t t_begin, uint32_t t_end,
+                           hipStream_t stream)
 {
     const DeviceTables *tab = nullptr;
     hzp_status_t st = device_tables(plan, &tab);
     if (st != HZP_OK) return st;
     // Tensors travel in the argument block, kUnpackTensorCap at a time; pieces are sorted by tensor.
     size_t p0 = 0;
-    for (uint32_t t0 = 0; t0 < b.n_tensors; t0 += kUnpackTensorCap) {
-        const uint32_t t1 = std::min<uint32_t>(b.n_tensors, t0 + kUnpackTensorCap);
+    while (p0 < b.pieces.size() && b.pieces[p0].tensor < t_begin) ++p0;
+    for (uint32_t t0 = t_begin; t0 < t_end; t0 += kUnpackTensorCap) {
+        const uint32_t t1 = std::min<uint32_t>(t_end, t0 + kUnpackTensorCap);
         size_t p1 = p0;
         while (p1 < b.pieces.size() && b.pieces[p1].tensor < t1) ++p1;
         UnpackArgs a{};
         for (uint32_t s = 0; s < n_shards; ++s) a.shard[s] = shards[s];
-        for (uint32_t t = t0; t < t1; ++t) a.tensor[t - t0] = tensors[t];
+        for (uint32_t t = t0; t < t1; ++t) a.tensor[t - t0] = tensors[t - t_begin];
         a.pieces = tab->pieces + b.piece_slot;
         a.piece_chunk = tab->piece_chunk + b.piece_slot;
         a.n_pieces = (uint32_t)b.pieces.size();

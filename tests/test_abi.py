@@ -129,6 +129,17 @@ def test_gather_argument_errors():
     assert _status(f, loose, 0, 0, 1, [FAKE] * 2, FAKE, None, stream=0) == hzp.HZP_ERR_UNSUPPORTED
 
 
+def test_gather_tensor_argument_errors():
+    p = _plan()
+    f = hzp.hzp_gather_tensor
+    assert _status(f, p, 3, [FAKE] * 2, FAKE, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 0, [FAKE], FAKE, stream=0) == hzp.HZP_ERR_INVALID_ARG           # needs Z3 = 2 entries
+    assert _status(f, p, 0, [FAKE] * 2, 0, stream=0) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(f, p, 0, [0, 0], FAKE, stream=0) == hzp.HZP_ERR_INVALID_ARG            # the shard it lies in
+    assert _status(f, p, 0, [FAKE + 8, FAKE], FAKE, stream=0) == hzp.HZP_ERR_ALIGN
+    assert _status(f, p, 0, [FAKE] * 2, FAKE + 1, stream=0) == hzp.HZP_ERR_ALIGN          # bf16 needs 2-byte alignment
+
+
 def test_gather_shard_argument_errors():
     p = hzp.hzp_plan([1], [100], align=8, z3=4, z1=6, z2=2)          # S1 = 32, S3 = 48: two owners per shard
     f = hzp.hzp_gather_shard

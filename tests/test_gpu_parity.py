@@ -512,3 +512,32 @@ def test_update_can_write_straight_into_the_zero3_shard():
     got = to_host(shard3, np.uint16)
     assert_bf16_within_one_ulp(got[k * S1:(k + 1) * S1], want16, "piece in the shard", po)
     assert (got[:k * S1] == 0x7FC1).all() and (got[(k + 1) * S1:] == 0x7FC1).all()
+
+
+def test_gather_one_parameter_at_a_time():
+    """Per-parameter gather (the granularity Section 4.2 prefers): every tensor of an irregular plan
+    rebuilt on its own from the shards it meets -- the other shard entries are NULL -- into an
+    output that is only element-aligned."""
+    say("gather_tensor")
+    desc = hzp_inputs.irregular_desc(40, seed=70, max_numel=30000, tensors_per_layer=8)
+    z3 = 4
+    oplan, plan = oracle_plan(desc, 8, z3, 8), lib_plan(desc, 8, z3, 8)
+    rng = np.random.default_rng(71)
+    for b in oplan["buckets"]:
+        cls, S3 = b["cls"], b["S3"]
+        ndt, tdt = (np.uint32, torch.int32) if cls == 1 else (np.uint16, torch.int16)
+        shards = [rng.integers(0, np.iinfo(ndt).max, size=S3, dtype=np.uint64).astype(ndt) for _ in range(z3)]
+        dshards = [to_dev(x) for x in shards]
+        for t in b["tensor_ids"]:
+            rec = oplan["tensors"][t]
+            j0, j1 = rec["offset"] // S3, (rec["offset"] + rec["numel"] - 1) // S3
+            ptrs = [dshards[j] if j0 <= j <= j1 else None for j in range(z3)]
+            shift = t % 5                                              # element-aligned, mostly not 16-byte aligned
+            whole, out = guarded(rec["numel"] + shift, tdt)
+            view = out[shift:]
+            hzp.hzp_gather_tensor(plan, t, ptrs, view)
+            torch.cuda.synchronize()
+            want = on.unpack_tensor(shards, rec["offset"], rec["numel"])
+            assert np.array_equal(to_host(view, ndt), want), t
+            poison = 0x7FC1 if cls == 0 else 0x7FC12345
+            assert (to_host(out[:shift], ndt) == poison).all() and guards_intact(whole, rec["numel"] + shift), t
