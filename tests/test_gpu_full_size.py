@@ -152,3 +152,65 @@ def test_irregular_4096_tensors_full():
         assert np.array_equal(got[1:1 + total], want), bi
         assert got[0] == 0 and got[1 + total] == 0
         assert np.array_equal(to_host(full, np_dt), on.gather_concat(shards)), bi
+
+
+def test_free_group_gather_at_dense7b_size_as_benchmarked():
+    """`bench.py --secondary freegroups`: the dense7b layers under Z1 = 12, Z3 = 8, ZeRO-3 shard 1 of
+    every layer rebuilt from one partial and one whole ZeRO-1 shard.  Whole output against the
+    device's own slices; oracle-computed windows at both ends and at the seam between the owners."""
+    cfg = hzp_inputs.config(1)
+    n_layers = 4
+    w = bench.Workload(cfg, n_layers, cfg["z3"] + 1, torch, hzp, hzp_inputs)
+    bench.add_secondary_buffers(w, ["freegroups"])
+    stream = torch.cuda.Stream()
+    say("free-group gather at dense7b size, Z1=%d" % w.free_z1)
+    bench.run_secondary(w, hzp, stream, "freegroups")
+    stream.synchronize()
+    tpl = cfg["tensors_per_layer"][:n_layers]
+    oplan = op.make_plan(tpl, cfg["tensor_numel"][:sum(tpl)], cfg["align"], cfg["z3"], w.free_z1)
+    for (l, _, dst, owners), ob in zip(w.free_args, oplan["buckets"]):
+        cover = op.cover(oplan, ob, 1)
+        assert len(cover) == len(owners) == 2 and w.free_plan.cover(l, 0, 1) == (cover[0][0], 2)
+        parts = [_bits16(o)[src:src + n] for o, (_, src, _, n) in zip(owners, cover)]
+        assert torch.equal(_bits16(dst), torch.cat(parts)), l
+        S1, S3 = ob["S1"], ob["S3"]
+        first = cover[0][0]
+        for x0 in (0, cover[1][2] - 40, S3 - 80):                         # start, owner seam, end
+            want = [0] * 80
+            for x in range(x0, x0 + 80):                                   # the definition, element by element
+                pos = S3 + x
+                i = pos // S1
+                want[x - x0] = int(to_host(_bits16(owners[i - first])[pos - i * S1:pos - i * S1 + 1], np.uint16)[0])
+            got = to_host(_bits16(dst)[x0:x0 + 80], np.uint16)
+            assert got.tolist() == want, (l, x0)
+
+
+def test_single_parameter_gather_at_dense7b_size():
+    """One 11008 x 4096 projection that straddles ZeRO-3 shards, gathered on its own."""
+    cfg = hzp_inputs.config(1)
+    w = bench.Workload(cfg, 3, cfg["z3"] + 1, torch, hzp, hzp_inputs)
+    stream = torch.cuda.Stream()
+    bench.run_step(w, hzp, 1, stream, {"gather3"})         # fills the layer buckets from the same shards
+    layer = 1
+    grads, p, m, v, out, owners, shard3, shards, bucket = w.keep[layer]
+    b = w.buckets[layer]
+    first_tid = sum(cfg["tensors_per_layer"][:layer])
+    recs = [w.plan.tensor(first_tid + t) for t in range(b.n_tensors)]
+    big = [r for r in recs if r.numel == 11008 * 4096 and r.offset // b.s3 != (r.offset + r.numel - 1) // b.s3]
+    assert big
+    rec = big[0]
+    tid = first_tid + recs.index(rec)
+    say("gather_tensor at full size: tensor %d, %d elements" % (tid, rec.numel))
+    j0, j1 = rec.offset // b.s3, (rec.offset + rec.numel - 1) // b.s3
+    ptrs = [shards[j] if j0 <= j <= j1 else None for j in range(w.z3)]
+    pool = torch.zeros(rec.numel + 9, dtype=torch.int16, device=DEV)
+    view = pool[5:5 + rec.numel]
+    hzp.hzp_gather_tensor(w.plan, tid, ptrs, view, stream=stream.cuda_stream)
+    stream.synchronize()
+    assert torch.equal(view, _bits16(bucket)[rec.offset:rec.offset + rec.numel])
+    host_shards = [to_host(_bits16(s), np.uint16) for s in shards]
+    seam = (j0 + 1) * b.s3 - rec.offset
+    for start in (0, seam - 40, rec.numel - 80):
+        want = on.unpack_tensor(host_shards, int(rec.offset) + int(start), 80)
+        assert np.array_equal(to_host(view[start:start + 80], np.uint16), want), start
+    assert not to_host(pool[:5], np.uint16).any() and not to_host(pool[5 + rec.numel:], np.uint16).any()
