@@ -42,9 +42,9 @@ typedef enum {
     HZP_OK = 0,
     HZP_ERR_INVALID_ARG = 1,    /* NULL where a pointer is required, inconsistent counts, step 0 ... */
     HZP_ERR_RANGE = 2,          /* layer / rank / tensor id / level outside the plan */
-    HZP_ERR_UNSUPPORTED = 3,    /* a valid request this build does not cover (e.g. Z3 does not divide Z1) */
+    HZP_ERR_UNSUPPORTED = 3,    /* a valid request this build does not cover (e.g. more than 32 contributions) */
     HZP_ERR_ALIGN = 4,          /* a device pointer is not aligned as the entry point requires */
-    HZP_ERR_NOMEM = 5,
+    HZP_ERR_NOMEM = 5,          /* host or device allocation failed; a full scheduler pool; no group sizes fit */
     HZP_ERR_HIP = 6             /* a HIP runtime call or a kernel launch failed */
 } hzp_status_t;
 
