@@ -25,6 +25,33 @@ def test_header_symbols_are_exported():
         assert hasattr(lib, n), n
 
 
+def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path):
+    """hzp.h compiles as C99 with no other include, and a C program's sizeof/offsetof of every
+    struct the binding mirrors agree with the ctypes declarations."""
+    import subprocess
+    from paper_2510_20111_amd import binding as bd
+    pairs = [("hzp_plan_desc_t", bd.PlanDesc), ("hzp_plan_info_t", bd.PlanInfo), ("hzp_bucket_info_t", bd.BucketInfo),
+             ("hzp_tensor_info_t", bd.TensorInfo), ("hzp_adamw_t", bd.AdamW), ("hzp_sched_desc_t", bd.SchedDesc),
+             ("hzp_sched_stats_t", bd.SchedStats)]
+    lines = ['#include "hzp.h"', "#include <stdio.h>", "#include <stddef.h>", "int main(void) {"]
+    for cname, ct in pairs:
+        lines.append('printf("%s %%zu", sizeof(%s));' % (cname, cname))
+        for fname, _ in ct._fields_:
+            lines.append('printf(" %%zu", offsetof(%s, %s));' % (cname, fname))
+        lines.append('printf("\\n");')
+    lines.append("return 0; }")
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    for (cname, ct), line in zip(pairs, out):
+        got = line.split()
+        want = [cname, str(ctypes.sizeof(ct))] + [str(getattr(ct, f).offset) for f, _ in ct._fields_]
+        assert got == want, cname
+
+
 def test_binding_has_the_same_names():
     for n in ("hzp_plan", "hzp_plan_free", "hzp_reduce_shard", "hzp_adamw_shard",
               "hzp_gather_layer", "hzp_last_error"):
