@@ -33,6 +33,8 @@ def parse_args():
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--separate-allocations", action="store_true",
                     help="give every slice its own allocation instead of per-kind arenas (layout experiment)")
+    ap.add_argument("--gather1-per-layer", action="store_true",
+                    help="issue the level-1 gather as one call per layer instead of one call for all layers")
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
@@ -82,6 +84,7 @@ class Workload:
         self.payload_params = 0           # tensor elements; the rest of p_total is padding
         g_ptrs, p_ptrs, m_ptrs, v_ptrs, o_ptrs = [], [], [], [], []
         self.l1_args, self.l3_args = [], []
+        l1_src, l1_dst = [], []
         tid = 0
         for l, b in enumerate(self.buckets):
             ranges = []
@@ -113,10 +116,14 @@ class Workload:
             g_ptrs += grads
             p_ptrs.append(p); m_ptrs.append(m); v_ptrs.append(v); o_ptrs.append(out)
             self.l1_args.append((l, hzp.ptr_array(owners), shard3.data_ptr()))
+            l1_src += owners
+            l1_dst.append(shard3)
             self.l3_args.append((l, hzp.ptr_array(shards), bucket.data_ptr()))
+        self.l1_all = (hzp.ptr_array(l1_src), hzp.ptr_array(l1_dst))       # the post-step gather of all layers in one call
         self.arenas = arenas
         self._piece, self._torch, self._hzp, self._dev = piece, torch, hzp, dev
         self.unpack_args, self.reduce_args = None, None
+        self.l1_per_layer = False
         self.g_arr, self.p_arr = hzp.ptr_array(g_ptrs), hzp.ptr_array(p_ptrs)
         self.m_arr, self.v_arr, self.o_arr = hzp.ptr_array(m_ptrs), hzp.ptr_array(v_ptrs), hzp.ptr_array(o_ptrs)
         # the same update as one call per layer (the secondary row "perlayer")
@@ -327,8 +334,11 @@ def run_step(w, hzp, step, stream, phases, events=None):
     if events:
         events[1].record(stream)
     if "gather1" in phases:
-        for l, arr, dst in w.l1_args:
-            hzp.hzp_gather_layer(w.plan, l, 0, 1, arr, dst, None, stream=s)
+        if w.l1_per_layer:
+            for l, arr, dst in w.l1_args:
+                hzp.hzp_gather_layer(w.plan, l, 0, 1, arr, dst, None, stream=s)
+        else:       # the post-step gather runs for every layer at once (Section 4.1.2, Optimizer Step)
+            hzp.hzp_gather_layers(w.plan, 0, w.n_layers, 0, 1, w.l1_all[0], w.K, w.l1_all[1], stream=s)
     if events:
         events[2].record(stream)
     if "gather3" in phases:
@@ -454,6 +464,7 @@ def main():
     n_layers = len(cfg["tensors_per_layer"]) if args.layers <= 0 else min(args.layers, len(cfg["tensors_per_layer"]))
     rank = cfg["z3"] + 1 if cfg["z1"] > cfg["z3"] + 1 else 0      # a rank with j = 1, k = 1
     w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations)
+    w.l1_per_layer = args.gather1_per_layer
     phases = set(args.phases.split(","))
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -495,8 +506,13 @@ def main():
         rooflines["fused_adamw"] = roof("fused_adamw_kernel<R=%d,bf16>" % R, fused_bytes, fused_ms,
                                         fused_launches, "fused_adamw_%s" % cfg["name"])
     if "gather1" in phases:
-        rooflines["gather_level1"] = roof("concat_kernel (K=%d x S1 -> S3)" % w.K, g1_bytes, g1_ms,
-                                          w.n_layers, "concat_l1_%s" % cfg["name"])
+        if w.l1_per_layer:
+            rooflines["gather_level1"] = roof("concat_kernel (K=%d x S1 -> S3)" % w.K, g1_bytes, g1_ms,
+                                              w.n_layers, "concat_l1_%s" % cfg["name"])
+        else:
+            per_launch = min(40, 320 // w.K)        # layers one launch of the layer-range gather holds
+            rooflines["gather_level1"] = roof("concat_layers_kernel (all layers, K=%d x S1 -> S3)" % w.K, g1_bytes,
+                                              g1_ms, -(-w.n_layers // per_launch), "concat_layers_l1_%s" % cfg["name"])
     if "gather3" in phases:
         rooflines["gather_level3"] = roof("concat_kernel (Z3=%d x S3 -> P)" % w.z3, g3_bytes, g3_ms,
                                           w.n_layers, "concat_l3_%s" % cfg["name"])
@@ -511,8 +527,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d layer buckets, R=%d, Z3=%d, Z1=%d, A=%d, rank %d; step = fused "
-                               "reduce+AdamW on the S1 shards + level-1 gather + level-3 gather"
-                               % (cfg["name"], w.n_layers, R, w.z3, cfg["z1"], cfg["align"], rank),
+                               "reduce+AdamW on the S1 shards + level-1 gather (%s) + level-3 gather per layer"
+                               % (cfg["name"], w.n_layers, R, w.z3, cfg["z1"], cfg["align"], rank,
+                                  "one call per layer" if w.l1_per_layer else "all layers in one call"),
                    "shard_params_per_step": w.s1_total, "padded_params": w.p_total,
                    "payload_params": w.payload_params, "padding_params": w.p_total - w.payload_params,
                    "phases": sorted(phases)},
@@ -530,6 +547,7 @@ def main():
         result["scheduler_overlap"] = overlap_probe(w, hzp, torch, stream)
     if secondary:
         add_secondary_buffers(w, secondary)
+        torch.cuda.synchronize()        # the new buffers were filled on the default stream
         result["secondary"] = {}
         for phase in secondary:
             ms = time_secondary(w, hzp, torch, stream, phase, args.steps, args.warmup)

@@ -275,6 +275,21 @@ hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer, uint32_t c
                               void *const *tensor_out, hipStream_t stream);
 
 /* ------------------------------------------------------------------------------------------
+ * hzp_gather_layer's bucket output for a range of layers in one call (one kernel launch for up
+ * to 40 layers): the post-step gather of Section 4.1.2 runs for every layer at once, and many
+ * small launches leave the memory system idle between them.
+ *   shard_ptrs : host array [(layer_end-layer_begin) * n_shards]; entry (l*n_shards + s) is shard s
+ *                of layer layer_begin+l, as in hzp_gather_layer; entries of layers that have no
+ *                bucket of the class are not read
+ *   bucket_out : host array [layer_end-layer_begin] of device pointers (S3 elements at level 1,
+ *                P at level 3), 16-byte aligned
+ * Errors: as hzp_gather_layer; INVALID_ARG for an empty layer range.
+ * ------------------------------------------------------------------------------------------ */
+hzp_status_t hzp_gather_layers(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, uint32_t cls,
+                               int level, const void *const *shard_ptrs, uint32_t n_shards,
+                               void *const *bucket_out, hipStream_t stream);
+
+/* ------------------------------------------------------------------------------------------
  * Gather of one parameter: the all-gather at parameter granularity that Section 4.2 prefers to
  * whole buckets.  Rebuilds tensor `tensor_id` (numbering of hzp_plan_tensor) from the ZeRO-3 shards
  * of its bucket:

@@ -21,7 +21,7 @@ _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSU
 
 EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
            "hzp_plan_rank", "hzp_plan_index", "hzp_plan_cover", "hzp_plan_shard", "hzp_plan_bytes",
-           "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_shard", "hzp_gather_tensor", "hzp_last_error",
+           "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_layers", "hzp_gather_shard", "hzp_gather_tensor", "hzp_last_error",
            "hzp_memory_model", "hzp_choose_groups",
            "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_acquire",
            "hzp_sched_release", "hzp_sched_reduce", "hzp_sched_join", "hzp_sched_drain", "hzp_sched_stats"]
@@ -112,6 +112,8 @@ def _load():
     L.hzp_plan_cover.argtypes = [vp, u32, u32, u32, u32p, u32p]
     L.hzp_gather_shard.restype = ctypes.c_int
     L.hzp_gather_shard.argtypes = [vp, u32, u32, u32, vp, u32, vp, vp]
+    L.hzp_gather_layers.restype = ctypes.c_int
+    L.hzp_gather_layers.argtypes = [vp, u32, u32, u32, ctypes.c_int, vp, u32, vp, vp]
     L.hzp_gather_tensor.restype = ctypes.c_int
     L.hzp_gather_tensor.argtypes = [vp, u32, vp, u32, vp, vp]
     L.hzp_plan_shard.restype = ctypes.c_int
@@ -312,6 +314,11 @@ def hzp_gather_shard(plan, layer, cls, j, owner_ptrs, shard_out, stream=None, n_
     arr = ptr_array(owner_ptrs)
     _check(_L.hzp_gather_shard(plan.handle, layer, cls, j, arr, len(arr) if n_owners is None else n_owners,
                                _addr(shard_out), _stream(stream)))
+
+
+def hzp_gather_layers(plan, layer_begin, layer_end, cls, level, shard_ptrs, n_shards, bucket_out, stream=None):
+    _check(_L.hzp_gather_layers(plan.handle, layer_begin, layer_end, cls, level, ptr_array(shard_ptrs), n_shards,
+                                ptr_array(bucket_out), _stream(stream)))
 
 
 def hzp_gather_tensor(plan, tensor_id, shard_ptrs, tensor_out, stream=None, n_shards=None):

@@ -214,3 +214,54 @@ extern "C" hzp_status_t hzp_gather_tensor(const hzp_plan_t *plan, uint32_t tenso
     void *out[1] = {tensor_out};
     return launch_unpack(plan, b, sh, n_shards, out, t.index_in_bucket, t.index_in_bucket + 1, stream);
 }
+
+extern "C" hzp_status_t hzp_gather_layers(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                                          uint32_t cls, int level, const void *const *shard_ptrs,
+                                          uint32_t n_shards, void *const *bucket_out, hipStream_t stream)
+{
+    if (!plan || !shard_ptrs || !bucket_out)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layers: NULL plan, shard array or output array");
+    if (layer_begin >= layer_end)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layers: empty layer range [%u, %u)", layer_begin, layer_end);
+    if (layer_end > plan->n_layers)
+        return fail(HZP_ERR_RANGE, "hzp_gather_layers: layer_end %u of %u", layer_end, plan->n_layers);
+    if (cls > 1) return fail(HZP_ERR_RANGE, "hzp_gather_layers: class %u", cls);
+    if (level != 1 && level != 3)
+        return fail(HZP_ERR_RANGE, "hzp_gather_layers: level %d is neither 1 nor 3", level);
+    if (level == 1 && plan->K == 0)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layers: z3=%u does not divide z1=%u; use hzp_gather_shard",
+                    plan->z3, plan->z1);
+    const uint32_t want = level == 1 ? plan->K : plan->z3;
+    if (n_shards != want)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layers: level %d takes %u shards per layer, got %u", level,
+                    want, n_shards);
+    if (n_shards > HZP_MAX_GROUP)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layers: %u shards exceed %u", n_shards, HZP_MAX_GROUP);
+    const uint32_t es = cls == HZP_CLASS_F32 ? 4u : 2u;
+    std::vector<const void *> src;
+    std::vector<void *> dst;
+    std::vector<uint64_t> bytes;
+    try {
+        for (uint32_t layer = layer_begin; layer < layer_end; ++layer) {
+            const BucketRec *b = find_bucket(plan, layer, cls);
+            if (!b) continue;                   // this layer has no tensor of the class
+            const size_t idx = layer - layer_begin;
+            if (!bucket_out[idx]) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layers: layer %u: NULL output", layer);
+            if (!aligned16(bucket_out[idx]))
+                return fail(HZP_ERR_ALIGN, "hzp_gather_layers: layer %u: output not 16-byte aligned", layer);
+            for (uint32_t s = 0; s < n_shards; ++s) {
+                const void *p = shard_ptrs[idx * n_shards + s];
+                if (!p) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layers: layer %u: shard %u is NULL", layer, s);
+                if (!aligned16(p))
+                    return fail(HZP_ERR_ALIGN, "hzp_gather_layers: layer %u: shard %u not 16-byte aligned", layer, s);
+                src.push_back(p);
+            }
+            dst.push_back(bucket_out[idx]);
+            bytes.push_back((level == 1 ? b->S1 : b->S3) * es);
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(HZP_ERR_NOMEM, "hzp_gather_layers: out of host memory");
+    }
+    if (dst.empty()) return HZP_OK;
+    return launch_concat_layers(src.data(), n_shards, bytes.data(), dst.data(), (uint32_t)dst.size(), stream);
+}

@@ -99,6 +99,9 @@ hzp_status_t launch_fused(const hzp_plan_t *plan, bool g32, bool o32, uint32_t R
                           size_t nseg, const hzp_adamw_t &hy, hipStream_t stream);
 hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t bytes_per_shard, void *dst,
                            hipStream_t stream);
+// Concatenates `per_layer` equal pieces for each of n_layers layers; srcs[l*per_layer + k], dsts[l].
+hzp_status_t launch_concat_layers(const void *const *srcs, uint32_t per_layer, const uint64_t *bytes_per_piece,
+                                  void *const *dsts, uint32_t n_layers, hipStream_t stream);
 // Copies n pieces of different lengths: piece s goes from srcs[s] to dst + dst_off[s] (bytes, all
 // multiples of 16).
 hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_off, const uint64_t *bytes,

@@ -448,6 +448,29 @@ __global__ __launch_bounds__(kWave) void concat_kernel(const ConcatArgs a)
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(val) : "memory");
 }
 
+// The same copy for the buckets of many layers in one launch (the post-step gather runs for all
+// layers at once; 34 launches of 16 us each leave the memory system idle between them).
+// grid = (tiles of the longest piece, pieces of all layers); piece s belongs to layer s / per_layer.
+constexpr int kLayersPieceCap = 320;
+constexpr int kLayersCap = 40;
+struct ConcatLayersArgs {
+    const void *src[kLayersPieceCap];
+    u32x4 *dst[kLayersCap];
+    uint32_t nvec[kLayersCap];      // vectors per piece of the layer
+    uint32_t per_layer;             // pieces per layer
+};
+__global__ __launch_bounds__(kWave) void concat_layers_kernel(const ConcatLayersArgs a)
+{
+    const uint32_t s = blockIdx.y;
+    const uint32_t layer = s / a.per_layer, k = s - layer * a.per_layer;
+    const uint32_t n = a.nvec[layer];
+    const uint32_t vec = blockIdx.x * kWave + threadIdx.x;
+    if (vec >= n) return;
+    const u32x4 val = ld_stream(reinterpret_cast<const u32x4 *>(a.src[s]) + vec);
+    u32x4 *dst = a.dst[layer] + (size_t)k * n + vec;
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(val) : "memory");
+}
+
 // The same copy for pieces of different lengths (a ZeRO-3 shard rebuilt from whole and partial
 // ZeRO-1 shards when the group sizes do not nest).  One-dimensional grid over the 64-vector tiles
 // of all pieces; a workgroup finds its piece by scanning the tile prefix (at most HZP_MAX_GROUP
@@ -737,6 +760,33 @@ hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t 
     const dim3 grid((uint32_t)((nvec + kWave - 1) / kWave), n_shards), block(kWave);
     hipLaunchKernelGGL(concat_kernel, grid, block, 0, stream, a);
     return check_launch("hzp_gather_layer");
+}
+
+hzp_status_t launch_concat_layers(const void *const *srcs, uint32_t per_layer, const uint64_t *bytes_per_piece,
+                                  void *const *dsts, uint32_t n_layers, hipStream_t stream)
+{
+    const uint32_t layers_per_launch = std::min<uint32_t>(kLayersCap, kLayersPieceCap / per_layer);
+    for (uint32_t l0 = 0; l0 < n_layers; l0 += layers_per_launch) {
+        const uint32_t cnt = std::min(layers_per_launch, n_layers - l0);
+        ConcatLayersArgs a{};
+        uint64_t longest = 0;
+        for (uint32_t l = 0; l < cnt; ++l) {
+            const uint64_t nvec = bytes_per_piece[l0 + l] / 16;
+            if (nvec > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layers: shard larger than 64 GiB");
+            a.nvec[l] = (uint32_t)nvec;
+            a.dst[l] = reinterpret_cast<u32x4 *>(dsts[l0 + l]);
+            longest = std::max(longest, nvec);
+            for (uint32_t k = 0; k < per_layer; ++k)
+                a.src[l * per_layer + k] = srcs[(size_t)(l0 + l) * per_layer + k];
+        }
+        a.per_layer = per_layer;
+        if (longest == 0) continue;
+        const dim3 grid((uint32_t)((longest + kWave - 1) / kWave), cnt * per_layer), block(kWave);
+        hipLaunchKernelGGL(concat_layers_kernel, grid, block, 0, stream, a);
+        hzp_status_t st = check_launch("hzp_gather_layers");
+        if (st != HZP_OK) return st;
+    }
+    return HZP_OK;
 }
 
 hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_off, const uint64_t *bytes,

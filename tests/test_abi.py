@@ -156,6 +156,23 @@ def test_gather_argument_errors():
     assert _status(f, loose, 0, 0, 1, [FAKE] * 2, FAKE, None, stream=0) == hzp.HZP_ERR_UNSUPPORTED
 
 
+def test_gather_layers_argument_errors():
+    p = _plan()                      # 2 layers; z3 = 2, K = 2; layer 1 has no fp32 bucket
+    f = hzp.hzp_gather_layers
+    two = [FAKE] * 4
+    assert _status(f, p, 0, 0, 0, 3, two, 2, [FAKE] * 2, stream=0) == hzp.HZP_ERR_INVALID_ARG      # empty range
+    assert _status(f, p, 0, 3, 0, 3, two, 2, [FAKE] * 2, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 0, 2, 2, 3, two, 2, [FAKE] * 2, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 0, 2, 0, 2, two, 2, [FAKE] * 2, stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 0, 2, 0, 3, two, 3, [FAKE] * 2, stream=0) == hzp.HZP_ERR_INVALID_ARG      # Z3 = 2 per layer
+    assert _status(f, p, 0, 2, 0, 3, [FAKE, FAKE, FAKE, 0], 2, [FAKE] * 2, stream=0) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(f, p, 0, 2, 0, 3, [FAKE, FAKE + 4, FAKE, FAKE], 2, [FAKE] * 2, stream=0) == hzp.HZP_ERR_ALIGN
+    assert _status(f, p, 0, 2, 0, 3, two, 2, [FAKE, 0], stream=0) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(f, p, 0, 2, 0, 1, two, 2, [FAKE, FAKE + 2], stream=0) == hzp.HZP_ERR_ALIGN
+    loose = hzp.hzp_plan([1], [100], align=8, z3=4, z1=6, z2=2)
+    assert _status(f, loose, 0, 1, 0, 1, [FAKE] * 2, 2, [FAKE], stream=0) == hzp.HZP_ERR_UNSUPPORTED
+
+
 def test_gather_tensor_argument_errors():
     p = _plan()
     f = hzp.hzp_gather_tensor

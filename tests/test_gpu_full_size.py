@@ -163,6 +163,7 @@ def test_free_group_gather_at_dense7b_size_as_benchmarked():
     w = bench.Workload(cfg, n_layers, cfg["z3"] + 1, torch, hzp, hzp_inputs)
     bench.add_secondary_buffers(w, ["freegroups"])
     stream = torch.cuda.Stream()
+    torch.cuda.synchronize()            # the buffers were filled on the default stream
     say("free-group gather at dense7b size, Z1=%d" % w.free_z1)
     bench.run_secondary(w, hzp, stream, "freegroups")
     stream.synchronize()
@@ -190,6 +191,7 @@ def test_single_parameter_gather_at_dense7b_size():
     cfg = hzp_inputs.config(1)
     w = bench.Workload(cfg, 3, cfg["z3"] + 1, torch, hzp, hzp_inputs)
     stream = torch.cuda.Stream()
+    torch.cuda.synchronize()            # the buffers were filled on the default stream
     bench.run_step(w, hzp, 1, stream, {"gather3"})         # fills the layer buckets from the same shards
     layer = 1
     grads, p, m, v, out, owners, shard3, shards, bucket = w.keep[layer]

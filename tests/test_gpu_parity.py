@@ -541,3 +541,41 @@ def test_gather_one_parameter_at_a_time():
             assert np.array_equal(to_host(view, ndt), want), t
             poison = 0x7FC1 if cls == 0 else 0x7FC12345
             assert (to_host(out[:shift], ndt) == poison).all() and guards_intact(whole, rec["numel"] + shift), t
+
+
+@pytest.mark.parametrize("level", [1, 3])
+def test_gather_many_layers_in_one_call(level):
+    """A layer range in one call (more layers than one launch holds, buckets of different
+    lengths, layers without a bucket of the class) equals the per-layer definition."""
+    say("gather_layers level", level)
+    desc = hzp_inputs.irregular_desc(90, seed=80, max_numel=20000, tensors_per_layer=2, f32_every=3)
+    z3, z1 = 4, 8
+    oplan, plan = oracle_plan(desc, 8, z3, z1), lib_plan(desc, 8, z3, z1)
+    n_layers, K = oplan["n_layers"], oplan["K"]
+    assert n_layers == 45
+    rng = np.random.default_rng(81)
+    per = K if level == 1 else z3
+    for cls in (0, 1):
+        ndt, tdt = (np.uint32, torch.int32) if cls == 1 else (np.uint16, torch.int16)
+        for lo, hi in ((0, n_layers), (3, 44), (7, 8)):
+            host, ptrs, outs = {}, [], []
+            for layer in range(lo, hi):
+                b = op.find_bucket(oplan, layer, cls)
+                if b is None:
+                    ptrs += [None] * per
+                    outs.append((None, None, 0))
+                    continue
+                n = b["S1"] if level == 1 else b["S3"]
+                pieces = [rng.integers(0, np.iinfo(ndt).max, size=n, dtype=np.uint64).astype(ndt) for _ in range(per)]
+                host[layer] = pieces
+                dp = [to_dev(x) for x in pieces]
+                outs.append(guarded(per * n, tdt) + (per * n,))
+                ptrs += dp
+            assert hi - lo < 10 or cls == 0 or any(o[1] is None for o in outs)      # some layers lack fp32 buckets
+            hzp.hzp_gather_layers(plan, lo, hi, cls, level, ptrs, per, [o[1] for o in outs])
+            torch.cuda.synchronize()
+            for layer, (whole, view, n) in zip(range(lo, hi), outs):
+                if view is None:
+                    continue
+                assert np.array_equal(to_host(view, ndt), on.gather_concat(host[layer])), (cls, layer)
+                assert guards_intact(whole, n), (cls, layer)
