@@ -207,6 +207,7 @@ def test_single_parameter_gather_at_dense7b_size():
     ptrs = [shards[j] if j0 <= j <= j1 else None for j in range(w.z3)]
     pool = torch.zeros(rec.numel + 9, dtype=torch.int16, device=DEV)
     view = pool[5:5 + rec.numel]
+    torch.cuda.synchronize()            # pool was cleared on the default stream
     hzp.hzp_gather_tensor(w.plan, tid, ptrs, view, stream=stream.cuda_stream)
     stream.synchronize()
     assert torch.equal(view, _bits16(bucket)[rec.offset:rec.offset + rec.numel])
