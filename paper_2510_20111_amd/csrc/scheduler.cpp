@@ -358,6 +358,20 @@ extern "C" hzp_status_t hzp_sched_reduce(hzp_sched_t *s, uint32_t layer, int lev
     if (R == 0 || R > HZP_MAX_REPLICAS) return fail(HZP_ERR_UNSUPPORTED, "hzp_sched_reduce: R=%u", R);
     if (!find_bucket(s->plan, layer, s->cls))
         return fail(HZP_ERR_RANGE, "hzp_sched_reduce: no bucket (layer %u, class %u)", layer, s->cls);
+    // Everything hzp_reduce_shard would refuse is refused here, at submission: an error found
+    // later, on the background thread, could only be reported by failing the whole scheduler.
+    if (level < 1 || level > 3) return fail(HZP_ERR_RANGE, "hzp_sched_reduce: level %d is not 1, 2 or 3", level);
+    if (rank >= s->plan->world)
+        return fail(HZP_ERR_RANGE, "hzp_sched_reduce: rank %u of %u", rank, s->plan->world);
+    if (grad_dtype > HZP_GRAD_F32)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_sched_reduce: unknown gradient type %u", grad_dtype);
+    for (uint32_t r = 0; r < R; ++r) {
+        if (!grad_slices[r]) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_reduce: slice %u is NULL", r);
+        if (reinterpret_cast<uintptr_t>(grad_slices[r]) & 15u)
+            return fail(HZP_ERR_ALIGN, "hzp_sched_reduce: slice %u is not 16-byte aligned", r);
+    }
+    if (reinterpret_cast<uintptr_t>(out_f32) & 15u)
+        return fail(HZP_ERR_ALIGN, "hzp_sched_reduce: output is not 16-byte aligned");
     std::unique_lock<std::mutex> lock(s->mu);
     if (s->failed != HZP_OK) return fail(s->failed, "scheduler failed earlier: %s", s->fail_text);
     Cmd cmd;

@@ -105,6 +105,19 @@ def test_protocol_errors_and_back_pressure():
     got = to_host(view16(ptr, oplan["buckets"][2]["P"]).clone(), np.uint16)
     assert np.array_equal(got, on.gather_concat(shards[2]))
     sched.release(2)
+    # a refused reduction leaves the scheduler usable (it is refused at submission, not on the thread)
+    g = [torch.zeros(64, dtype=torch.int16, device=DEV)]
+    out = torch.zeros(64, device=DEV)
+    assert status(sched.reduce, 0, 4, 0, g, 1.0, False, out) == hzp.HZP_ERR_RANGE            # level
+    assert status(sched.reduce, 0, 3, 99, g, 1.0, False, out) == hzp.HZP_ERR_RANGE           # rank
+    assert status(sched.reduce, 0, 3, 0, [g[0][1:]], 1.0, False, out) == hzp.HZP_ERR_ALIGN
+    assert status(sched.reduce, 0, 3, 0, g, 1.0, False, out[1:]) == hzp.HZP_ERR_ALIGN
+    sched.prefetch(3, dshards[3])
+    ptr = sched.acquire(3)
+    sched.drain()
+    assert np.array_equal(to_host(view16(ptr, oplan["buckets"][3]["P"]).clone(), np.uint16), on.gather_concat(shards[3]))
+    sched.release(3)
+    assert sched.stats().reduces_issued == 0
     sched.destroy()
     with pytest.raises(hzp.HzpError):
         hzp.Sched(plan, gather_slots=0)
