@@ -329,34 +329,43 @@ hzp_status_t hzp_gather_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t c
 /* ------------------------------------------------------------------------------------------
  * Asynchronous scheduler: the multi-stream dispatch of Section 4.2 for the local halves of the
  * collectives.  A scheduler owns one background host thread, two dedicated streams (gathers,
- * reductions; default priority) and a fixed-capacity persistent pool of `gather_slots` contiguous
- * layer-bucket buffers that are reused cyclically.  Issuing a prefetch or a reduction returns at
- * once and puts nothing on the caller's compute stream; the compute stream waits for a layer's
- * parameters only where it acquires them, and a slot is given back right after its use.
+ * reductions; default priority) and a fixed-capacity persistent pool: one contiguous buffer,
+ * allocated once, that the gathers use as a ring.  Issuing a prefetch or a reduction returns at
+ * once and puts nothing on the caller's compute stream; the compute stream waits for gathered
+ * parameters only where it acquires them, and their space is given back right after their use.
  *
- * Protocol per layer: prefetch -> acquire -> (use on `consumer`) -> release.  Layers must be
- * released in the order they were prefetched (the pool is a cycle), and at most `gather_slots`
- * layers can be between prefetch and release: one more prefetch returns HZP_ERR_NOMEM (back
- * pressure) instead of blocking.  Host-side waits inside these calls are bounded (30 s) and then
- * fail with HZP_ERR_HIP; after any failure every later call on the scheduler returns that status.
- * All calls may come from one thread at a time; the plan must outlive the scheduler.
+ * Protocol per layer (or per parameter, the granularity Section 4.2 prefers):
+ *     prefetch -> acquire -> (use on `consumer`) -> release.
+ * A prefetch takes the next region of the ring, a release returns it; space comes back oldest
+ * first, so regions should be released in the order they were prefetched (one released early keeps
+ * its place until everything older is released).  When the ring has no room, or `gather_slots`
+ * regions are live already, a prefetch returns HZP_ERR_NOMEM (back pressure) instead of blocking.
+ * Host-side waits inside these calls are bounded (30 s) and then fail with HZP_ERR_HIP; after any
+ * failure every later call on the scheduler returns that status.  All calls may come from one
+ * thread at a time; the plan must outlive the scheduler.
  * ------------------------------------------------------------------------------------------ */
 typedef struct hzp_sched hzp_sched_t;
 
 typedef struct {
     uint32_t cls;               /* class of the buckets this scheduler gathers and reduces */
-    uint32_t gather_slots;      /* pool capacity in layer buckets = how far prefetch can run ahead, >= 1 */
+    uint32_t gather_slots;      /* most regions between prefetch and release at once, >= 1 */
     uint32_t queue_capacity;    /* commands that may wait for the background thread, >= 1 */
+    uint32_t reserved_;         /* 0 */
+    uint64_t pool_bytes;        /* 0: the ring is gather_slots equal slots of the largest bucket, so any
+                                 * gather_slots regions fit.  Otherwise the ring's size (a multiple of 256):
+                                 * a region then takes its own size rounded up to 256 bytes, and a prefetch
+                                 * is also refused while the free space is split between the two ends */
 } hzp_sched_desc_t;
 
 typedef struct {
     uint64_t pool_bytes;            /* size of the persistent pool (allocated once) */
-    uint64_t slot_bytes;            /* size of one slot: the largest bucket, rounded to 256 bytes */
-    uint64_t peak_live_bytes;       /* most bucket bytes that were between prefetch and release at once */
-    uint32_t peak_live_slots;
+    uint64_t slot_bytes;            /* the largest bucket of the class, rounded to 256 bytes */
+    uint64_t peak_live_bytes;       /* most gathered bytes that were between prefetch and release at once */
+    uint32_t peak_live_slots;       /* most regions between prefetch and release at once */
     uint32_t reserved_;
     uint64_t gathers_issued, reduces_issued;
     uint64_t acquire_host_wait_us;  /* host time spent in acquire waiting for the gather to be issued */
+    uint64_t wrap_skipped_bytes;    /* ring space passed over, in total, where a region did not fit before the end */
 } hzp_sched_stats_t;
 
 /* Allocates the pool on the current device and starts the thread.  Errors: INVALID_ARG, RANGE
@@ -364,16 +373,24 @@ typedef struct {
 hzp_status_t hzp_sched_create(const hzp_plan_t *plan, const hzp_sched_desc_t *desc, hzp_sched_t **out);
 /* Launches what is still queued, waits for the side streams, frees everything.  NULL allowed. */
 void hzp_sched_destroy(hzp_sched_t *sched);
-/* Queue the level-3 gather of `layer` (hzp_gather_layer with bucket_out = the next pool slot).
- * shard_ptrs: host array [Z3] of device pointers, copied.  Returns at once. */
+/* Queue the level-3 gather of `layer` (hzp_gather_layer with bucket_out = the next region of the
+ * ring).  shard_ptrs: host array [Z3] of device pointers, copied.  Returns at once. */
 hzp_status_t hzp_sched_prefetch(hzp_sched_t *sched, uint32_t layer, const void *const *shard_ptrs, uint32_t n_shards);
 /* Make `consumer` wait for the layer's gather and return the bucket's device address.  Blocks the
  * host only until the background thread has launched that gather. */
 hzp_status_t hzp_sched_acquire(hzp_sched_t *sched, uint32_t layer, hipStream_t consumer, void **bucket);
 /* The work enqueued on `consumer` so far is the last use of the layer's bucket. */
 hzp_status_t hzp_sched_release(hzp_sched_t *sched, uint32_t layer, hipStream_t consumer);
+/* The same three calls for one parameter (hzp_gather_tensor into the next region of the ring;
+ * shard_ptrs as there: entries of shards the tensor does not lie in may be NULL).  A tensor and the
+ * layer it belongs to are separate regions. */
+hzp_status_t hzp_sched_prefetch_tensor(hzp_sched_t *sched, uint32_t tensor_id, const void *const *shard_ptrs,
+                                       uint32_t n_shards);
+hzp_status_t hzp_sched_acquire_tensor(hzp_sched_t *sched, uint32_t tensor_id, hipStream_t consumer, void **tensor);
+hzp_status_t hzp_sched_release_tensor(hzp_sched_t *sched, uint32_t tensor_id, hipStream_t consumer);
 /* Queue hzp_reduce_shard(layer, level, rank, ...) on the reduction stream, to run after the work
- * already enqueued on `producer` (which wrote the gradients).  Pointer array copied.  Returns at once. */
+ * already enqueued on `producer` (which wrote the gradients).  Arguments are checked now, as by
+ * hzp_reduce_shard; the pointer array is copied.  Returns at once. */
 hzp_status_t hzp_sched_reduce(hzp_sched_t *sched, uint32_t layer, int level, uint32_t rank,
                               const void *const *grad_slices, uint32_t R, uint32_t grad_dtype, float scale,
                               int accumulate, float *out_f32, hipStream_t producer);

@@ -24,7 +24,8 @@ EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_info", "hzp_plan_bucket", "hzp
            "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_layers", "hzp_gather_shard", "hzp_gather_tensor", "hzp_last_error",
            "hzp_memory_model", "hzp_choose_groups",
            "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_acquire",
-           "hzp_sched_release", "hzp_sched_reduce", "hzp_sched_join", "hzp_sched_drain", "hzp_sched_stats"]
+           "hzp_sched_release", "hzp_sched_prefetch_tensor", "hzp_sched_acquire_tensor",
+           "hzp_sched_release_tensor", "hzp_sched_reduce", "hzp_sched_join", "hzp_sched_drain", "hzp_sched_stats"]
 
 
 class HzpError(RuntimeError):
@@ -67,14 +68,16 @@ class TensorInfo(ctypes.Structure):
 
 class SchedDesc(ctypes.Structure):
     _fields_ = [("cls", ctypes.c_uint32), ("gather_slots", ctypes.c_uint32),
-                ("queue_capacity", ctypes.c_uint32)]
+                ("queue_capacity", ctypes.c_uint32), ("reserved_", ctypes.c_uint32),
+                ("pool_bytes", ctypes.c_uint64)]
 
 
 class SchedStats(ctypes.Structure):
     _fields_ = [("pool_bytes", ctypes.c_uint64), ("slot_bytes", ctypes.c_uint64),
                 ("peak_live_bytes", ctypes.c_uint64), ("peak_live_slots", ctypes.c_uint32),
                 ("reserved_", ctypes.c_uint32), ("gathers_issued", ctypes.c_uint64),
-                ("reduces_issued", ctypes.c_uint64), ("acquire_host_wait_us", ctypes.c_uint64)]
+                ("reduces_issued", ctypes.c_uint64), ("acquire_host_wait_us", ctypes.c_uint64),
+                ("wrap_skipped_bytes", ctypes.c_uint64)]
 
 
 class AdamW(ctypes.Structure):
@@ -142,6 +145,12 @@ def _load():
     L.hzp_sched_acquire.argtypes = [vp, u32, vp, ctypes.POINTER(vp)]
     L.hzp_sched_release.restype = ctypes.c_int
     L.hzp_sched_release.argtypes = [vp, u32, vp]
+    L.hzp_sched_prefetch_tensor.restype = ctypes.c_int
+    L.hzp_sched_prefetch_tensor.argtypes = [vp, u32, vp, u32]
+    L.hzp_sched_acquire_tensor.restype = ctypes.c_int
+    L.hzp_sched_acquire_tensor.argtypes = [vp, u32, vp, ctypes.POINTER(vp)]
+    L.hzp_sched_release_tensor.restype = ctypes.c_int
+    L.hzp_sched_release_tensor.argtypes = [vp, u32, vp]
     L.hzp_sched_reduce.restype = ctypes.c_int
     L.hzp_sched_reduce.argtypes = [vp, u32, ctypes.c_int, u32, vp, u32, u32, ctypes.c_float, ctypes.c_int, vp, vp]
     L.hzp_sched_join.restype = ctypes.c_int
@@ -330,9 +339,9 @@ def hzp_gather_tensor(plan, tensor_id, shard_ptrs, tensor_out, stream=None, n_sh
 class Sched:
     """Owner of an ``hzp_sched_t*`` (hzp_sched_create ... hzp_sched_destroy)."""
 
-    def __init__(self, plan, cls=HZP_CLASS_BF16, gather_slots=2, queue_capacity=64):
+    def __init__(self, plan, cls=HZP_CLASS_BF16, gather_slots=2, queue_capacity=64, pool_bytes=0):
         self.plan = plan                      # keeps the plan alive
-        desc = SchedDesc(cls, gather_slots, queue_capacity)
+        desc = SchedDesc(cls, gather_slots, queue_capacity, 0, pool_bytes)
         self.handle = ctypes.c_void_p()
         _check(_L.hzp_sched_create(plan.handle, ctypes.byref(desc), ctypes.byref(self.handle)))
 
@@ -354,6 +363,18 @@ class Sched:
 
     def release(self, layer, consumer=None):
         _check(_L.hzp_sched_release(self.handle, layer, _stream(consumer)))
+
+    def prefetch_tensor(self, tensor_id, shard_ptrs):
+        arr = ptr_array(shard_ptrs)
+        _check(_L.hzp_sched_prefetch_tensor(self.handle, tensor_id, arr, len(arr)))
+
+    def acquire_tensor(self, tensor_id, consumer=None):
+        out = ctypes.c_void_p()
+        _check(_L.hzp_sched_acquire_tensor(self.handle, tensor_id, _stream(consumer), ctypes.byref(out)))
+        return out.value
+
+    def release_tensor(self, tensor_id, consumer=None):
+        _check(_L.hzp_sched_release_tensor(self.handle, tensor_id, _stream(consumer)))
 
     def reduce(self, layer, level, rank, grad_slices, scale, accumulate, out_f32, producer=None,
                grad_dtype=HZP_GRAD_DEFAULT):

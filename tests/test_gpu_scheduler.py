@@ -167,3 +167,130 @@ def test_hungry_reduce_after_the_producer_and_join():
                                    want[layer][bad[:8]].tolist())
     assert sched.stats().reduces_issued == 3 * rounds
     sched.destroy()
+
+
+def _ring_model(cap, live, nbytes):
+    """Where the next region of a ring goes: live = [(off, bytes)] oldest first.  None if no room."""
+    if nbytes > cap:
+        return None
+    if not live:
+        return 0
+    tail, head = live[0][0], live[-1][0] + live[-1][1]
+    if head > tail:
+        if head + nbytes <= cap:
+            return head
+        return 0 if nbytes <= tail else None
+    return head if head + nbytes <= tail else None
+
+
+def test_ring_pool_with_layers_of_different_sizes():
+    """Buckets of very different sizes move through a ring that is smaller than three of the largest:
+    every bucket arrives intact, regions follow the ring arithmetic, and space is lost only at wraps."""
+    say("scheduler: ring pool, ragged layers")
+    rng = np.random.default_rng(60)
+    n_layers = 14
+    numel = [int(x) for x in rng.choice([3000, 20000, 90000, 150000], size=n_layers)]
+    numel[0], numel[5] = 150000, 150000
+    desc = dict(tensors_per_layer=[1] * n_layers, tensor_numel=numel)
+    oplan, plan = oracle_plan(desc, 8, 4, 8), lib_plan(desc, 8, 4, 8)
+    shards, dshards = [], []
+    for b in oplan["buckets"]:
+        bucket = rng.integers(0, 1 << 16, size=b["P"], dtype=np.uint64).astype(np.uint16)
+        shards.append([np.ascontiguousarray(bucket[j * b["S3"]:(j + 1) * b["S3"]]) for j in range(4)])
+        dshards.append([to_dev(s) for s in shards[-1]])
+    sizes = [(2 * b["P"] + 255) // 256 * 256 for b in oplan["buckets"]]
+    cap = 2 * max(sizes) + 4096
+    sched = hzp.Sched(plan, gather_slots=4, queue_capacity=8, pool_bytes=cap)
+    consumer = torch.cuda.Stream()
+    outs = [torch.zeros(b["P"], dtype=torch.int16, device=DEV) for b in oplan["buckets"]]
+    torch.cuda.synchronize()
+    live, base, nxt, skipped = [], None, 0, 0
+
+    def try_prefetch():
+        nonlocal nxt, skipped
+        while nxt < n_layers and len(live) < 4:
+            off = _ring_model(cap, [(o, n) for _, o, n in live], sizes[nxt])
+            if off is None:
+                with pytest.raises(hzp.HzpError) as e:
+                    sched.prefetch(nxt, dshards[nxt])
+                assert e.value.status == hzp.HZP_ERR_NOMEM
+                return
+            if live and off == 0 and live[-1][1] + live[-1][2] > live[0][1]:
+                skipped += cap - (live[-1][1] + live[-1][2])
+            sched.prefetch(nxt, dshards[nxt])
+            live.append((nxt, off, sizes[nxt]))
+            nxt += 1
+
+    try_prefetch()
+    for l in range(n_layers):
+        assert live and live[0][0] == l
+        ptr = sched.acquire(l, consumer)
+        base = ptr - live[0][1] if base is None else base
+        assert ptr - base == live[0][1], (l, ptr - base, live[0])
+        with torch.cuda.stream(consumer):
+            outs[l].copy_(view16(ptr, outs[l].numel()))
+        sched.release(l, consumer)
+        live.pop(0)
+        try_prefetch()
+    consumer.synchronize()
+    sched.drain()
+    for l in range(n_layers):
+        assert np.array_equal(to_host(outs[l], np.uint16), on.gather_concat(shards[l])), l
+    st = sched.stats()
+    assert st.pool_bytes == cap and st.gathers_issued == n_layers
+    assert st.peak_live_bytes <= cap and 2 <= st.peak_live_slots <= 4
+    assert st.wrap_skipped_bytes == skipped and skipped > 0
+    sched.destroy()
+
+
+def test_prefetch_one_parameter_at_a_time():
+    """The paper's granularity: every tensor of a plan prefetched, acquired and released on its own,
+    three ahead, through a ring much smaller than a layer."""
+    say("scheduler: per-parameter prefetch")
+    desc = hzp_inputs.irregular_desc(30, seed=61, max_numel=40000, tensors_per_layer=6, f32_every=0)
+    desc = dict(desc, tensor_class=None, tensor_wd_mult=None)
+    z3 = 4
+    oplan, plan = oracle_plan(desc, 8, z3, 8), lib_plan(desc, 8, z3, 8)
+    rng = np.random.default_rng(62)
+    shards, dshards = {}, {}
+    for bi, b in enumerate(oplan["buckets"]):
+        bucket = rng.integers(0, 1 << 16, size=b["P"], dtype=np.uint64).astype(np.uint16)
+        shards[bi] = [np.ascontiguousarray(bucket[j * b["S3"]:(j + 1) * b["S3"]]) for j in range(z3)]
+        dshards[bi] = [to_dev(s) for s in shards[bi]]
+    n_t = len(oplan["tensors"])
+    biggest = max(t["numel"] for t in oplan["tensors"])
+    sched = hzp.Sched(plan, gather_slots=3, queue_capacity=8, pool_bytes=(3 * 2 * biggest + 255) // 256 * 256 + 512)
+    consumer = torch.cuda.Stream()
+    outs = [torch.zeros(t["numel"], dtype=torch.int16, device=DEV) for t in oplan["tensors"]]
+    torch.cuda.synchronize()
+
+    def ptrs_of(t):
+        rec = oplan["tensors"][t]
+        b = oplan["buckets"][rec["bucket"]]
+        j0, j1 = rec["offset"] // b["S3"], (rec["offset"] + rec["numel"] - 1) // b["S3"]
+        return [dshards[rec["bucket"]][j] if j0 <= j <= j1 else None for j in range(z3)]
+
+    for t in range(3):
+        sched.prefetch_tensor(t, ptrs_of(t))
+    with pytest.raises(hzp.HzpError) as e:
+        sched.prefetch_tensor(3, ptrs_of(3))
+    assert e.value.status == hzp.HZP_ERR_NOMEM                      # three regions are live
+    with pytest.raises(hzp.HzpError) as e:
+        sched.acquire(0)                                            # layer 0 was never prefetched, tensor 0 was
+    assert e.value.status == hzp.HZP_ERR_INVALID_ARG
+    for t in range(n_t):
+        ptr = sched.acquire_tensor(t, consumer)
+        with torch.cuda.stream(consumer):
+            outs[t].copy_(view16(ptr, outs[t].numel()))
+        sched.release_tensor(t, consumer)
+        if t + 3 < n_t:
+            sched.prefetch_tensor(t + 3, ptrs_of(t + 3))
+    consumer.synchronize()
+    sched.drain()
+    for t in range(n_t):
+        rec = oplan["tensors"][t]
+        want = on.unpack_tensor(shards[rec["bucket"]], rec["offset"], rec["numel"])
+        assert np.array_equal(to_host(outs[t], np.uint16), want), t
+    st = sched.stats()
+    assert st.gathers_issued == n_t and st.peak_live_slots == 3
+    sched.destroy()
