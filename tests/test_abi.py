@@ -213,3 +213,15 @@ def test_scheduler_argument_errors_before_any_gpu_call():
     with pytest.raises(hzp.HzpError) as e:
         hzp.Sched(only_bf16, cls=hzp.HZP_CLASS_F32)
     assert e.value.status == hzp.HZP_ERR_RANGE
+
+
+def test_shards_of_2_to_the_30_elements_are_refused_before_any_launch():
+    """Kernels address a slice with a 32-bit byte offset; the entry points refuse longer slices."""
+    big = hzp.hzp_plan([1], [1 << 31], align=8, z3=1, z1=2)          # S1 = 2^30, S3 = 2^31
+    hy = hzp.adamw_hyper(1e-4, 0.9, 0.95, 1e-8, 0.1, 1.0, 1)
+    one = [FAKE]
+    assert _status(hzp.hzp_reduce_shard, big, 0, 0, 1, 0, one, 1.0, 0, FAKE, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+    assert _status(hzp.hzp_reduce_shard, big, 0, 0, 3, 0, one, 1.0, 0, FAKE, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+    assert _status(hzp.hzp_adamw_shard, big, 0, 1, 0, 0, hy, one, 1, one, one, one, one, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+    ok = hzp.hzp_plan([1], [1 << 31], align=8, z3=1, z1=4)           # S1 = 2^29 passes the size check
+    assert ok.bucket(0).s1 == 1 << 29
