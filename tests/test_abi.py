@@ -225,3 +225,59 @@ def test_shards_of_2_to_the_30_elements_are_refused_before_any_launch():
     assert _status(hzp.hzp_adamw_shard, big, 0, 1, 0, 0, hy, one, 1, one, one, one, one, stream=0) == hzp.HZP_ERR_UNSUPPORTED
     ok = hzp.hzp_plan([1], [1 << 31], align=8, z3=1, z1=4)           # S1 = 2^29 passes the size check
     assert ok.bucket(0).s1 == 1 << 29
+
+
+def test_a_plain_c_program_can_plan_through_the_library(tmp_path):
+    """hzp.h + libhzp.so used from C without Python in between: plan, read-back, memory model."""
+    import subprocess
+    from oracle import planner as op
+    src = tmp_path / "plan.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include "hzp.h"
+int main(void) {
+    const uint32_t per_layer[2] = {2, 1};
+    const uint64_t numel[3] = {1000, 77, 4096};
+    hzp_plan_desc_t d = {2, per_layer, numel, NULL, NULL, 16, 4, 2, 6};      /* A=16, Z3=4, Z2=2, Z1=6 */
+    hzp_plan_t *plan = NULL;
+    if (hzp_plan(&d, &plan) != HZP_OK) { printf("error: %s\n", hzp_last_error()); return 1; }
+    hzp_plan_info_t info;
+    hzp_plan_info(plan, &info);
+    printf("%u %u %llu\n", info.world, info.k, (unsigned long long)info.total_padded);
+    for (uint32_t l = 0; l < 2; ++l) {
+        hzp_bucket_info_t b;
+        hzp_plan_bucket(plan, l, HZP_CLASS_BF16, &b);
+        printf("%llu %llu %llu %llu %llu\n", (unsigned long long)b.payload_end, (unsigned long long)b.padded,
+               (unsigned long long)b.s1, (unsigned long long)b.s2, (unsigned long long)b.s3);
+    }
+    uint32_t first, n;
+    hzp_plan_cover(plan, 0, HZP_CLASS_BF16, 1, &first, &n);
+    uint64_t bytes;
+    hzp_memory_model(7000000000ull, 64, 8, 8, &bytes);
+    uint32_t z1, z2, z3;
+    hzp_status_t st = hzp_choose_groups(7000000000ull, 64, 8, 22000000000ull, &z1, &z2, &z3);
+    printf("%u %u %llu %d %u %u %u\n", first, n, (unsigned long long)bytes, (int)st, z1, z2, z3);
+    d.align_elems = 12;
+    printf("%d\n", (int)hzp_plan(&d, &plan));                                 /* refused: not a power of two */
+    hzp_plan_free(plan);
+    return 0;
+}
+""")
+    exe = tmp_path / "plan"
+    libdir = os.path.dirname(hzp.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-l:libhzp.so", "-Wl,-rpath," + libdir, "-Wl,--allow-shlib-undefined"], check=True)
+    import torch
+    env = dict(os.environ)
+    env["LD_LIBRARY_PATH"] = os.pathsep.join([os.path.join(os.path.dirname(torch.__file__), "lib"), "/opt/rocm/lib",
+                                              env.get("LD_LIBRARY_PATH", "")])
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, env=env).stdout.split("\n")
+    want = op.make_plan([2, 1], [1000, 77, 4096], 16, 4, 6, 2)
+    assert out[0].split() == [str(want["world"]), str(want["K"]), str(want["total_padded"])]
+    for l in range(2):
+        b = want["buckets"][l]
+        assert [int(x) for x in out[1 + l].split()] == [b["payload_end"], b["P"], b["S1"], b["S2"], b["S3"]]
+    cover = op.cover(want, want["buckets"][0], 1)
+    mem = op.hzp_memory_bytes(7000000000, 64, 8, 8)
+    assert out[3].split() == [str(cover[0][0]), str(len(cover)), str(-(-mem.numerator // mem.denominator)), "0", "8", "4", "4"]
+    assert out[4].split() == [str(hzp.HZP_ERR_INVALID_ARG)]
