@@ -25,8 +25,8 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=1, help="workload index 0..4 (1 = 7B-class dense)")
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
