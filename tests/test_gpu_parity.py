@@ -448,6 +448,31 @@ def test_unpack_more_tensors_than_one_launch_carries():
     assert np.array_equal(got[1:1 + want.size], want) and got[0] == 0 and not got[1 + want.size:].any()
 
 
+@pytest.mark.parametrize("n_tensors", [63, 64, 65, 4095, 4097, 6000])
+def test_unpack_piece_search_depths(n_tensors):
+    """The kernel finds a chunk's piece by a 64-ary search: one round up to 64 pieces, two up to
+    4096, three beyond.  Piece counts on both sides of each boundary, some tensors longer than a chunk."""
+    say("unpack with %d tensors" % n_tensors)
+    rng = np.random.default_rng(140 + n_tensors)
+    numel = [int(x) for x in rng.integers(1, 24, size=n_tensors)]
+    for t in rng.integers(0, n_tensors, size=5):
+        numel[int(t)] = int(rng.integers(1100, 5000))                   # spans several 1024-element chunks
+    desc = dict(tensors_per_layer=[n_tensors], tensor_numel=numel)
+    oplan, plan = oracle_plan(desc, 8, 1, 1), lib_plan(desc, 8, 1, 1)   # Z3 = 1: one piece per tensor
+    b = oplan["buckets"][0]
+    bucket = rng.integers(0, 1 << 16, size=b["P"], dtype=np.uint64).astype(np.uint16)
+    pool = torch.zeros(sum(numel) + 8, dtype=torch.int16, device=DEV)
+    views, pos = [], 3
+    for n in numel:
+        views.append(pool[pos:pos + n])
+        pos += n
+    hzp.hzp_gather_layer(plan, 0, 0, 3, [to_dev(bucket)], None, views)
+    torch.cuda.synchronize()
+    want = np.concatenate([on.unpack_tensor([bucket], oplan["tensors"][t]["offset"], numel[t]) for t in range(n_tensors)])
+    got = to_host(pool, np.uint16)
+    assert np.array_equal(got[3:3 + want.size], want) and not got[:3].any() and not got[3 + want.size:].any()
+
+
 # ------------------------------------------------------------------------------ next rows
 
 def test_gradient_accumulation_with_fp32_gradients_then_prereduced_update():
