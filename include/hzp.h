@@ -275,6 +275,27 @@ hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer, uint32_t c
                               void *const *tensor_out, hipStream_t stream);
 
 /* ------------------------------------------------------------------------------------------
+ * hzp_gather_layer's per-tensor output (level 3) for callers that cannot allocate device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The lookup
+ * table of the bucket's tensor pieces, which hzp_gather_layer keeps in per-plan device memory that it
+ * allocates on first use, here goes into a fixed array inside the library's device image
+ * (HZP_STATIC_MAX_PIECES entries, 176 KiB, one copy per GPU held until the process ends), written
+ * on `stream` by small kernels that carry it in their arguments.  The call allocates and frees
+ * nothing, makes no host-to-device copy and does not synchronise.
+ *     tensor_out[t][y] = bucket[offset_t + y],   y < numel_t,   for every tensor t of the bucket
+ *   shard_ptrs, n_shards, tensor_out : as hzp_gather_layer at level 3 (tensor_out is required)
+ * All calls on one GPU share the one array, which keeps the last call's table: calls on different
+ * streams that may run at the same time race; calls on one stream are ordered and safe.
+ * Errors: INVALID_ARG, RANGE, ALIGN, HIP as hzp_gather_layer; UNSUPPORTED when the bucket has more
+ * than HZP_STATIC_MAX_PIECES pieces (a piece is a run of one tensor inside one ZeRO-3 shard: at
+ * most n_tensors + Z3 - 1 of them) or more than HZP_MAX_GROUP shards.
+ * ------------------------------------------------------------------------------------------ */
+#define HZP_STATIC_MAX_PIECES 4096u
+hzp_status_t hzp_gather_layer_static(const hzp_plan_t *plan, uint32_t layer, uint32_t cls,
+                                     const void *const *shard_ptrs, uint32_t n_shards,
+                                     void *const *tensor_out, hipStream_t stream);
+
+/* ------------------------------------------------------------------------------------------
  * hzp_gather_layer's bucket output for a range of layers in one call (one kernel launch for up
  * to 40 layers): the post-step gather of Section 4.1.2 runs for every layer at once, and many
  * small launches leave the memory system idle between them.

@@ -21,7 +21,7 @@ _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSU
 
 EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
            "hzp_plan_rank", "hzp_plan_index", "hzp_plan_cover", "hzp_plan_shard", "hzp_plan_bytes",
-           "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_layers", "hzp_gather_shard", "hzp_gather_tensor", "hzp_last_error",
+           "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_layer_static", "hzp_gather_layers", "hzp_gather_shard", "hzp_gather_tensor", "hzp_last_error",
            "hzp_memory_model", "hzp_choose_groups",
            "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_acquire",
            "hzp_sched_release", "hzp_sched_prefetch_tensor", "hzp_sched_acquire_tensor",
@@ -131,6 +131,8 @@ def _load():
                                   vp, vp, vp, vp, vp]
     L.hzp_gather_layer.restype = ctypes.c_int
     L.hzp_gather_layer.argtypes = [vp, u32, u32, ctypes.c_int, vp, u32, vp, vp, vp]
+    L.hzp_gather_layer_static.restype = ctypes.c_int
+    L.hzp_gather_layer_static.argtypes = [vp, u32, u32, vp, u32, vp, vp]
     L.hzp_memory_model.restype = ctypes.c_int
     L.hzp_memory_model.argtypes = [ctypes.c_uint64, u32, u32, u32, u64p]
     L.hzp_choose_groups.restype = ctypes.c_int
@@ -317,6 +319,12 @@ def hzp_gather_layer(plan, layer, cls, level, shard_ptrs, bucket_out=None, tenso
                                len(arr) if n_shards is None else n_shards, _addr(bucket_out),
                                ptr_array(tensor_out) if tensor_out is not None else None,
                                _stream(stream)))
+
+
+def hzp_gather_layer_static(plan, layer, cls, shard_ptrs, tensor_out, stream=None, n_shards=None):
+    arr = ptr_array(shard_ptrs)
+    _check(_L.hzp_gather_layer_static(plan.handle, layer, cls, arr, len(arr) if n_shards is None else n_shards,
+                                      ptr_array(tensor_out) if tensor_out is not None else None, _stream(stream)))
 
 
 def hzp_gather_shard(plan, layer, cls, j, owner_ptrs, shard_out, stream=None, n_owners=None):

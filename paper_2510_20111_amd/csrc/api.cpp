@@ -150,6 +150,32 @@ extern "C" hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer,
     return HZP_OK;
 }
 
+extern "C" hzp_status_t hzp_gather_layer_static(const hzp_plan_t *plan, uint32_t layer, uint32_t cls,
+                                                const void *const *shard_ptrs, uint32_t n_shards,
+                                                void *const *tensor_out, hipStream_t stream)
+{
+    if (!plan || !shard_ptrs || !tensor_out)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer_static: NULL plan, shard array or tensor array");
+    const BucketRec *b = find_bucket(plan, layer, cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_gather_layer_static: no bucket (layer %u, class %u)", layer, cls);
+    if (n_shards != plan->z3)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer_static: takes %u shards, got %u", plan->z3, n_shards);
+    if (n_shards > HZP_MAX_GROUP)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layer_static: %u shards exceed %u", n_shards, HZP_MAX_GROUP);
+    const uint32_t es = cls == HZP_CLASS_F32 ? 4u : 2u;
+    for (uint32_t s = 0; s < n_shards; ++s) {
+        if (!shard_ptrs[s]) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer_static: shard %u is NULL", s);
+        if (!aligned16(shard_ptrs[s]))
+            return fail(HZP_ERR_ALIGN, "hzp_gather_layer_static: shard %u is not 16-byte aligned", s);
+    }
+    for (uint32_t t = 0; t < b->n_tensors; ++t) {
+        if (!tensor_out[t]) return fail(HZP_ERR_INVALID_ARG, "hzp_gather_layer_static: tensor_out[%u] is NULL", t);
+        if (reinterpret_cast<uintptr_t>(tensor_out[t]) % es)
+            return fail(HZP_ERR_ALIGN, "hzp_gather_layer_static: tensor_out[%u] is not element-aligned", t);
+    }
+    return launch_unpack_static(*b, shard_ptrs, n_shards, tensor_out, stream);
+}
+
 extern "C" hzp_status_t hzp_gather_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, uint32_t j,
                                          const void *const *owner_ptrs, uint32_t n_owners, void *shard_out,
                                          hipStream_t stream)

@@ -110,6 +110,10 @@ hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_o
 hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const void *const *shards,
                            uint32_t n_shards, void *const *tensors, uint32_t t_begin, uint32_t t_end,
                            hipStream_t stream);
+// The same for all tensors of the bucket with the piece table in the library's fixed device array
+// (no allocation, no copy call); refuses buckets with more than HZP_STATIC_MAX_PIECES pieces.
+hzp_status_t launch_unpack_static(const BucketRec &b, const void *const *shards, uint32_t n_shards,
+                                  void *const *tensors, hipStream_t stream);
 // Tables for the current device (creates them on first use).  Defined with the launchers.
 hzp_status_t device_tables(const hzp_plan_t *plan, const DeviceTables **out);
 void free_device_tables(hzp_plan_t *plan);

@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstring>
 #ifdef HZP_TUNE
 #include <cstdlib>
 #endif
@@ -819,13 +820,12 @@ hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_o
     return check_launch("hzp_gather_shard");
 }
 
-hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const void *const *shards,
-                           uint32_t n_shards, void *const *tensors, uint32_t t_begin, uint32_t t_end,
-                           hipStream_t stream)
+// Launches of the unpack kernel for tensors [t_begin, t_end) of a bucket; `pieces` and `piece_chunk`
+// are device tables that hold the bucket's pieces from entry 0.
+static hzp_status_t launch_unpack_with(const Piece *pieces, const uint32_t *piece_chunk, const BucketRec &b,
+                                       const void *const *shards, uint32_t n_shards, void *const *tensors,
+                                       uint32_t t_begin, uint32_t t_end, hipStream_t stream, const char *who)
 {
-    const DeviceTables *tab = nullptr;
-    hzp_status_t st = device_tables(plan, &tab);
-    if (st != HZP_OK) return st;
     // Tensors travel in the argument block, kUnpackTensorCap at a time; pieces are sorted by tensor.
     size_t p0 = 0;
     while (p0 < b.pieces.size() && b.pieces[p0].tensor < t_begin) ++p0;
@@ -836,8 +836,8 @@ hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const voi
         UnpackArgs a{};
         for (uint32_t s = 0; s < n_shards; ++s) a.shard[s] = shards[s];
         for (uint32_t t = t0; t < t1; ++t) a.tensor[t - t0] = tensors[t - t_begin];
-        a.pieces = tab->pieces + b.piece_slot;
-        a.piece_chunk = tab->piece_chunk + b.piece_slot;
+        a.pieces = pieces;
+        a.piece_chunk = piece_chunk;
         a.n_pieces = (uint32_t)b.pieces.size();
         a.chunk0 = b.pieces[p0].chunk_begin;
         a.chunk_end = p1 < b.pieces.size() ? b.pieces[p1].chunk_begin : b.n_chunks;
@@ -848,11 +848,111 @@ hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const voi
             hipLaunchKernelGGL(unpack_kernel<4>, grid, block, 0, stream, a);
         else
             hipLaunchKernelGGL(unpack_kernel<2>, grid, block, 0, stream, a);
-        st = check_launch("hzp_gather_layer");
+        hzp_status_t st = check_launch(who);
         if (st != HZP_OK) return st;
         p0 = p1;
     }
     return HZP_OK;
+}
+
+hzp_status_t launch_unpack(const hzp_plan_t *plan, const BucketRec &b, const void *const *shards,
+                           uint32_t n_shards, void *const *tensors, uint32_t t_begin, uint32_t t_end,
+                           hipStream_t stream)
+{
+    const DeviceTables *tab = nullptr;
+    hzp_status_t st = device_tables(plan, &tab);
+    if (st != HZP_OK) return st;
+    return launch_unpack_with(tab->pieces + b.piece_slot, tab->piece_chunk + b.piece_slot, b, shards, n_shards,
+                              tensors, t_begin, t_end, stream, "hzp_gather_layer");
+}
+
+// ---------------------------------------------------------------------------------------
+// The same unpack for callers that must not allocate: the bucket's piece table is written, by a
+// small kernel that carries it in its arguments, into a fixed array in device memory instead of
+// the per-plan tables that device_tables() allocates on first use.
+// ---------------------------------------------------------------------------------------
+struct StaticTables {
+    Piece pieces[HZP_STATIC_MAX_PIECES];
+    uint32_t piece_chunk[HZP_STATIC_MAX_PIECES];
+};
+// One copy per GPU, at an address of its own, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticTables)];
+
+constexpr uint32_t kFillWords = 896;    // 3584 bytes of table per launch, in the argument block
+struct FillArgs {
+    uint32_t word[kFillWords];
+    uint32_t *dst;
+    uint32_t n;
+};
+__global__ __launch_bounds__(256) void table_fill_kernel(const FillArgs a)
+{
+    for (uint32_t i = threadIdx.x; i < a.n; i += 256) a.dst[i] = a.word[i];
+}
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+static hzp_status_t scratch_address(StaticTables **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(HZP_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(HZP_ERR_UNSUPPORTED, "device %d: more than %d devices", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(HZP_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = static_cast<StaticTables *>(g_scratch_ptr[dev]);
+    return HZP_OK;
+}
+
+// Enqueue the copy of `bytes` (a multiple of 4) of host data to device memory at `dst`.
+static hzp_status_t fill_table(void *dst, const void *src, size_t bytes, hipStream_t stream)
+{
+    const uint32_t *w = static_cast<const uint32_t *>(src);
+    size_t left = bytes / 4;
+    uint32_t *d = static_cast<uint32_t *>(dst);
+    while (left) {
+        FillArgs a;
+        a.n = (uint32_t)std::min<size_t>(left, kFillWords);
+        std::memcpy(a.word, w, (size_t)a.n * 4);
+        a.dst = d;
+        hipLaunchKernelGGL(table_fill_kernel, dim3(1), dim3(256), 0, stream, a);
+        hzp_status_t st = check_launch("hzp_gather_layer_static");
+        if (st != HZP_OK) return st;
+        w += a.n;
+        d += a.n;
+        left -= a.n;
+    }
+    return HZP_OK;
+}
+
+hzp_status_t launch_unpack_static(const BucketRec &b, const void *const *shards, uint32_t n_shards,
+                                  void *const *tensors, hipStream_t stream)
+{
+    if (b.pieces.size() > HZP_STATIC_MAX_PIECES)
+        return fail(HZP_ERR_UNSUPPORTED,
+                    "hzp_gather_layer_static: the bucket has %zu tensor pieces, the fixed table holds %u; "
+                    "use hzp_gather_layer",
+                    b.pieces.size(), (unsigned)HZP_STATIC_MAX_PIECES);
+    StaticTables *tab = nullptr;
+    hzp_status_t st = scratch_address(&tab);
+    if (st != HZP_OK) return st;
+    uint32_t chunk_begin[HZP_STATIC_MAX_PIECES];
+    for (size_t i = 0; i < b.pieces.size(); ++i) chunk_begin[i] = b.pieces[i].chunk_begin;
+    static_assert(sizeof(Piece) % 4 == 0, "tables are copied in 32-bit words");
+    st = fill_table(tab->pieces, b.pieces.data(), b.pieces.size() * sizeof(Piece), stream);
+    if (st == HZP_OK) st = fill_table(tab->piece_chunk, chunk_begin, b.pieces.size() * sizeof(uint32_t), stream);
+    if (st != HZP_OK) return st;
+    return launch_unpack_with(tab->pieces, tab->piece_chunk, b, shards, n_shards, tensors, 0, b.n_tensors, stream,
+                              "hzp_gather_layer_static");
 }
 
 // ---------------------------------------------------------------------------------------
