@@ -33,6 +33,8 @@ def parse_args():
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--separate-allocations", action="store_true",
                     help="give every slice its own allocation instead of per-kind arenas (layout experiment)")
+    ap.add_argument("--one-allocation", type=int, default=-1, metavar="SKEW",
+                    help="carve every arena from one allocation, consecutive arenas SKEW bytes further apart (experiment)")
     ap.add_argument("--gather1-per-layer", action="store_true",
                     help="issue the level-1 gather as one call per layer instead of one call for all layers")
     ap.add_argument("--phases", default="fused,gather1,gather3",
@@ -51,7 +53,7 @@ class Workload:
     bucket's slice is the plan's `base` divided by the group size.  `separate=True` gives every
     slice its own allocation instead (a layout experiment: it streams about 4 % slower)."""
 
-    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False):
+    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False, one_alloc_skew=-1):
         self.cfg, self.rank = cfg, rank
         dev = "cuda:0"
         tpl = cfg["tensors_per_layer"][:n_layers]
@@ -67,10 +69,23 @@ class Workload:
         j, k, i = self.plan.rank(rank)
         bf16, f32 = torch.bfloat16, torch.float32
         arenas = {}
+        up = lambda b: (b + (2 << 20) - 1) // (2 << 20) * (2 << 20) + max(one_alloc_skew, 0)
+        self.one_alloc_bytes = (self.R * up(2 * self.s1_total) + 3 * up(4 * self.s1_total) + self.K * up(2 * self.s1_total)
+                                + (self.z3 + 1) * up(2 * self.s3_total) + up(2 * self.p_total) + (4 << 20))
+
+        big = {"buf": None, "off": 0}
 
         def arena(name, total, dtype):
             if name not in arenas:
-                arenas[name] = torch.empty(total, dtype=dtype, device=dev)
+                if one_alloc_skew >= 0:
+                    if big["buf"] is None:
+                        big["buf"] = torch.empty(self.one_alloc_bytes, dtype=torch.uint8, device=dev)
+                    nbytes = total * (2 if dtype == bf16 else 4)
+                    arenas[name] = big["buf"][big["off"]:big["off"] + nbytes].view(dtype)
+                    big["off"] += (nbytes + (2 << 20) - 1) // (2 << 20) * (2 << 20) + one_alloc_skew
+                    assert big["off"] <= self.one_alloc_bytes
+                else:
+                    arenas[name] = torch.empty(total, dtype=dtype, device=dev)
             return arenas[name]
 
         def piece(name, total, dtype, begin, n, fill=None):
@@ -506,7 +521,7 @@ def main():
     cfg = hzp_inputs.config(args.config)
     n_layers = len(cfg["tensors_per_layer"]) if args.layers <= 0 else min(args.layers, len(cfg["tensors_per_layer"]))
     rank = cfg["z3"] + 1 if cfg["z1"] > cfg["z3"] + 1 else 0      # a rank with j = 1, k = 1
-    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations)
+    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations, one_alloc_skew=args.one_allocation)
     w.l1_per_layer = args.gather1_per_layer
     phases = set(args.phases.split(","))
     stream = torch.cuda.Stream()

@@ -15,8 +15,9 @@
  *   - "device pointer": memory the current HIP device can address; "host array":
  *     ordinary host memory read during the call and not retained;
  *   - all device buffers are owned by the caller.  The library allocates device
- *     memory only for small per-plan lookup tables, created on the first call
- *     that needs them (that one call may synchronise) and freed by hzp_plan_free;
+ *     memory only for small per-plan lookup tables, created by hzp_plan_prepare
+ *     (or, without it, by the first call that needs them: that one call blocks)
+ *     and freed by hzp_plan_free, and for a scheduler's pool;
  *   - kernel work is enqueued on the given stream and the call returns at once;
  *     a plan is immutable and may be used from several host threads and streams
  *     at the same time (the paper issues these operations from extra threads on
@@ -146,6 +147,17 @@ hzp_status_t hzp_plan(const hzp_plan_desc_t *desc, hzp_plan_t **out);
 /* Free a plan and its device tables.  NULL is allowed.  The caller must make sure that no kernel
  * launched with this plan is still running. */
 void hzp_plan_free(hzp_plan_t *plan);
+
+/* Create the plan's lookup tables on the current device now (tensor offsets and decay multipliers
+ * for updates with per-tensor decay, tensor pieces for the unpacking gathers): one allocation and
+ * one blocking copy per table.  This is the one call on a plan that may allocate device memory and
+ * synchronise; after it has returned, no kernel-launching call with this plan on this device
+ * allocates, copies or waits (without it, the first call that needs a table creates it, and that
+ * call blocks).  `stream` is waited for before returning, together with the copies, so that work
+ * enqueued afterwards on any stream finds the tables in place.  May be called again (no effect) and
+ * from several threads.  Call it once per device that uses the plan.
+ * Errors: INVALID_ARG (NULL), NOMEM, HIP. */
+hzp_status_t hzp_plan_prepare(const hzp_plan_t *plan, hipStream_t stream);
 
 /* Read-back of the layout (what the tests compare with the oracle, bit for bit). */
 hzp_status_t hzp_plan_info(const hzp_plan_t *plan, hzp_plan_info_t *out);
@@ -371,7 +383,9 @@ typedef struct {
     uint32_t cls;               /* class of the buckets this scheduler gathers and reduces */
     uint32_t gather_slots;      /* most regions between prefetch and release at once, >= 1 */
     uint32_t queue_capacity;    /* commands that may wait for the background thread, >= 1 */
-    uint32_t reserved_;         /* 0 */
+    uint32_t copy_engine;       /* 0: bucket gathers are copy kernels; 1: they are device-to-device copies
+                                 * (hipMemcpyAsync per shard) on the gather stream, which the copy engines
+                                 * carry out without occupying compute units */
     uint64_t pool_bytes;        /* 0: the ring is gather_slots equal slots of the largest bucket, so any
                                  * gather_slots regions fit.  Otherwise the ring's size (a multiple of 256):
                                  * a region then takes its own size rounded up to 256 bytes, and a prefetch
@@ -389,14 +403,28 @@ typedef struct {
     uint64_t wrap_skipped_bytes;    /* ring space passed over, in total, where a region did not fit before the end */
 } hzp_sched_stats_t;
 
-/* Allocates the pool on the current device and starts the thread.  Errors: INVALID_ARG, RANGE
- * (no bucket of that class), NOMEM, HIP. */
+/* Allocates the pool on the current device, creates the plan's device tables (hzp_plan_prepare) and
+ * starts the thread: the only scheduler call that allocates or blocks on the device.
+ * Errors: INVALID_ARG, RANGE (no bucket of that class), NOMEM, HIP. */
 hzp_status_t hzp_sched_create(const hzp_plan_t *plan, const hzp_sched_desc_t *desc, hzp_sched_t **out);
 /* Launches what is still queued, waits for the side streams, frees everything.  NULL allowed. */
 void hzp_sched_destroy(hzp_sched_t *sched);
 /* Queue the level-3 gather of `layer` (hzp_gather_layer with bucket_out = the next region of the
- * ring).  shard_ptrs: host array [Z3] of device pointers, copied.  Returns at once. */
-hzp_status_t hzp_sched_prefetch(hzp_sched_t *sched, uint32_t layer, const void *const *shard_ptrs, uint32_t n_shards);
+ * ring).  shard_ptrs: host array [Z3] of device pointers, copied.  The gather runs after the work
+ * enqueued on `producer` before this call (the stream that wrote the shards: the optimizer step and
+ * the post-step gather of Section 4.1.2); an event is recorded there, nothing waits on it.
+ * Returns at once. */
+hzp_status_t hzp_sched_prefetch(hzp_sched_t *sched, uint32_t layer, const void *const *shard_ptrs, uint32_t n_shards,
+                                hipStream_t producer);
+/* Prefetch as far ahead as the pool allows: layers first_layer, first_layer+1, ... are queued in order
+ * until n_layers are queued or the pool has no room (Section 4.1.2, "Parameter Pre-fetching": how
+ * many all-gathers are issued in advance is governed by the available device memory).  *issued is
+ * the number of layers dealt with (layers without a bucket of the scheduler's class count as dealt
+ * with); a full pool is not an error here.
+ *   shard_ptrs : host array [n_layers * n_shards], entry (l*n_shards + j) is shard j of layer first_layer+l */
+hzp_status_t hzp_sched_prefetch_ahead(hzp_sched_t *sched, uint32_t first_layer, uint32_t n_layers,
+                                      const void *const *shard_ptrs, uint32_t n_shards, hipStream_t producer,
+                                      uint32_t *issued);
 /* Make `consumer` wait for the layer's gather and return the bucket's device address.  Blocks the
  * host only until the background thread has launched that gather. */
 hzp_status_t hzp_sched_acquire(hzp_sched_t *sched, uint32_t layer, hipStream_t consumer, void **bucket);
@@ -406,7 +434,7 @@ hzp_status_t hzp_sched_release(hzp_sched_t *sched, uint32_t layer, hipStream_t c
  * shard_ptrs as there: entries of shards the tensor does not lie in may be NULL).  A tensor and the
  * layer it belongs to are separate regions. */
 hzp_status_t hzp_sched_prefetch_tensor(hzp_sched_t *sched, uint32_t tensor_id, const void *const *shard_ptrs,
-                                       uint32_t n_shards);
+                                       uint32_t n_shards, hipStream_t producer);
 hzp_status_t hzp_sched_acquire_tensor(hzp_sched_t *sched, uint32_t tensor_id, hipStream_t consumer, void **tensor);
 hzp_status_t hzp_sched_release_tensor(hzp_sched_t *sched, uint32_t tensor_id, hipStream_t consumer);
 /* Queue hzp_reduce_shard(layer, level, rank, ...) on the reduction stream, to run after the work

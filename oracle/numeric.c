@@ -73,6 +73,12 @@ uint16_t hzp_oracle_f32_to_bf16(float f)
     return (uint16_t)kept;
 }
 
+/* The same cast over an array: out[x] = hzp_oracle_f32_to_bf16(in[x]). */
+void hzp_oracle_f32_to_bf16_array(const float *in, uint64_t n, uint16_t *out)
+{
+    for (uint64_t x = 0; x < n; ++x) out[x] = hzp_oracle_f32_to_bf16(in[x]);
+}
+
 /*
  * Gradient reduction over R contributions for one slice of n elements
  * (arithmetic half of the reduce-scatter plus the cross-replica reduction).

@@ -44,6 +44,8 @@ def lib():
         L.hzp_oracle_f32_to_bf16.restype = ctypes.c_uint16
         L.hzp_oracle_f32_to_bf16.argtypes = [ctypes.c_float]
         vp, u32, u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
+        L.hzp_oracle_f32_to_bf16_array.restype = None
+        L.hzp_oracle_f32_to_bf16_array.argtypes = [vp, u64, vp]
         L.hzp_oracle_reduce.restype = None
         L.hzp_oracle_reduce.argtypes = [vp, u32, ctypes.c_int, u64, ctypes.c_float,
                                         ctypes.c_int, vp]
@@ -95,6 +97,14 @@ def f32_to_bf16(f):
     flat_in, flat_out = f.reshape(-1), out.reshape(-1)
     for i in range(flat_in.size):
         flat_out[i] = L.hzp_oracle_f32_to_bf16(ctypes.c_float(flat_in[i]))
+    return out
+
+
+def f32_to_bf16_array(f):
+    """The same narrowing over a contiguous float32 array in one call (a loop over the scalar cast)."""
+    _check(f, np.float32)
+    out = np.empty(f.size, dtype=np.uint16)
+    lib().hzp_oracle_f32_to_bf16_array(_ptr(f), f.size, _ptr(out))
     return out
 
 

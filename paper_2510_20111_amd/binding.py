@@ -19,11 +19,11 @@ HZP_MAX_REPLICAS, HZP_MAX_GROUP = 32, 64
 _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSUPPORTED",
                  "HZP_ERR_ALIGN", "HZP_ERR_NOMEM", "HZP_ERR_HIP"]
 
-EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
+EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_prepare", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
            "hzp_plan_rank", "hzp_plan_index", "hzp_plan_cover", "hzp_plan_shard", "hzp_plan_bytes",
            "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_layer_static", "hzp_gather_layers", "hzp_gather_shard", "hzp_gather_tensor", "hzp_last_error",
            "hzp_memory_model", "hzp_choose_groups",
-           "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_acquire",
+           "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_prefetch_ahead", "hzp_sched_acquire",
            "hzp_sched_release", "hzp_sched_prefetch_tensor", "hzp_sched_acquire_tensor",
            "hzp_sched_release_tensor", "hzp_sched_reduce", "hzp_sched_join", "hzp_sched_drain", "hzp_sched_stats"]
 
@@ -68,7 +68,7 @@ class TensorInfo(ctypes.Structure):
 
 class SchedDesc(ctypes.Structure):
     _fields_ = [("cls", ctypes.c_uint32), ("gather_slots", ctypes.c_uint32),
-                ("queue_capacity", ctypes.c_uint32), ("reserved_", ctypes.c_uint32),
+                ("queue_capacity", ctypes.c_uint32), ("copy_engine", ctypes.c_uint32),
                 ("pool_bytes", ctypes.c_uint64)]
 
 
@@ -101,6 +101,8 @@ def _load():
     L.hzp_plan.argtypes = [ctypes.POINTER(PlanDesc), ctypes.POINTER(vp)]
     L.hzp_plan_free.restype = None
     L.hzp_plan_free.argtypes = [vp]
+    L.hzp_plan_prepare.restype = ctypes.c_int
+    L.hzp_plan_prepare.argtypes = [vp, vp]
     L.hzp_plan_info.restype = ctypes.c_int
     L.hzp_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
     L.hzp_plan_bucket.restype = ctypes.c_int
@@ -142,13 +144,15 @@ def _load():
     L.hzp_sched_destroy.restype = None
     L.hzp_sched_destroy.argtypes = [vp]
     L.hzp_sched_prefetch.restype = ctypes.c_int
-    L.hzp_sched_prefetch.argtypes = [vp, u32, vp, u32]
+    L.hzp_sched_prefetch.argtypes = [vp, u32, vp, u32, vp]
+    L.hzp_sched_prefetch_ahead.restype = ctypes.c_int
+    L.hzp_sched_prefetch_ahead.argtypes = [vp, u32, u32, vp, u32, vp, u32p]
     L.hzp_sched_acquire.restype = ctypes.c_int
     L.hzp_sched_acquire.argtypes = [vp, u32, vp, ctypes.POINTER(vp)]
     L.hzp_sched_release.restype = ctypes.c_int
     L.hzp_sched_release.argtypes = [vp, u32, vp]
     L.hzp_sched_prefetch_tensor.restype = ctypes.c_int
-    L.hzp_sched_prefetch_tensor.argtypes = [vp, u32, vp, u32]
+    L.hzp_sched_prefetch_tensor.argtypes = [vp, u32, vp, u32, vp]
     L.hzp_sched_acquire_tensor.restype = ctypes.c_int
     L.hzp_sched_acquire_tensor.argtypes = [vp, u32, vp, ctypes.POINTER(vp)]
     L.hzp_sched_release_tensor.restype = ctypes.c_int
@@ -214,6 +218,9 @@ class Plan:
         if getattr(self, "handle", None):
             _L.hzp_plan_free(self.handle)
             self.handle = None
+
+    def prepare(self, stream=None):
+        _check(_L.hzp_plan_prepare(self.handle, _stream(stream)))
 
     def info(self):
         out = PlanInfo()
@@ -347,9 +354,9 @@ def hzp_gather_tensor(plan, tensor_id, shard_ptrs, tensor_out, stream=None, n_sh
 class Sched:
     """Owner of an ``hzp_sched_t*`` (hzp_sched_create ... hzp_sched_destroy)."""
 
-    def __init__(self, plan, cls=HZP_CLASS_BF16, gather_slots=2, queue_capacity=64, pool_bytes=0):
+    def __init__(self, plan, cls=HZP_CLASS_BF16, gather_slots=2, queue_capacity=64, pool_bytes=0, copy_engine=False):
         self.plan = plan                      # keeps the plan alive
-        desc = SchedDesc(cls, gather_slots, queue_capacity, 0, pool_bytes)
+        desc = SchedDesc(cls, gather_slots, queue_capacity, int(bool(copy_engine)), pool_bytes)
         self.handle = ctypes.c_void_p()
         _check(_L.hzp_sched_create(plan.handle, ctypes.byref(desc), ctypes.byref(self.handle)))
 
@@ -360,9 +367,16 @@ class Sched:
 
     __del__ = destroy
 
-    def prefetch(self, layer, shard_ptrs):
+    def prefetch(self, layer, shard_ptrs, producer=None):
         arr = ptr_array(shard_ptrs)
-        _check(_L.hzp_sched_prefetch(self.handle, layer, arr, len(arr)))
+        _check(_L.hzp_sched_prefetch(self.handle, layer, arr, len(arr), _stream(producer)))
+
+    def prefetch_ahead(self, first_layer, n_layers, shard_ptrs, n_shards, producer=None):
+        """Queues layers first_layer.. as far as the pool allows; returns how many were dealt with."""
+        issued = ctypes.c_uint32()
+        _check(_L.hzp_sched_prefetch_ahead(self.handle, first_layer, n_layers, ptr_array(shard_ptrs), n_shards,
+                                           _stream(producer), ctypes.byref(issued)))
+        return issued.value
 
     def acquire(self, layer, consumer=None):
         out = ctypes.c_void_p()
@@ -372,9 +386,9 @@ class Sched:
     def release(self, layer, consumer=None):
         _check(_L.hzp_sched_release(self.handle, layer, _stream(consumer)))
 
-    def prefetch_tensor(self, tensor_id, shard_ptrs):
+    def prefetch_tensor(self, tensor_id, shard_ptrs, producer=None):
         arr = ptr_array(shard_ptrs)
-        _check(_L.hzp_sched_prefetch_tensor(self.handle, tensor_id, arr, len(arr)))
+        _check(_L.hzp_sched_prefetch_tensor(self.handle, tensor_id, arr, len(arr), _stream(producer)))
 
     def acquire_tensor(self, tensor_id, consumer=None):
         out = ctypes.c_void_p()

@@ -20,9 +20,7 @@
 
 #include <cmath>
 #include <cstring>
-#ifdef HZP_TUNE
-#include <cstdlib>
-#endif
+#include <vector>
 
 #include "hzp_internal.hpp"
 
@@ -65,6 +63,12 @@ __device__ __forceinline__ T *at(void *base, uint32_t idx)
 __device__ __forceinline__ void st_writethrough(void *base, uint32_t byte_off, f32x4 v)
 {
     asm volatile("global_store_dwordx4 %0, %1, %2 sc0 sc1 nt\n\ts_nop 1" ::"v"(byte_off), "v"(v), "s"(base) : "memory");
+}
+// The same store for a full 64-bit address in a VGPR pair (copy kernels, whose lanes compute their
+// own destination).
+__device__ __forceinline__ void st_writethrough(u32x4 *dst, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(v) : "memory");
 }
 __device__ __forceinline__ void st_writethrough(void *base, uint32_t byte_off, u32x2 v)
 {
@@ -344,10 +348,6 @@ __device__ __forceinline__ void fused_group(const void *const *sp, uint32_t R, c
     for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-#ifdef HZP_NO_MATH
-            m[hh][e] += g[hh][e]; v[hh][e] += g[hh][e]; p[hh][e] += g[hh][e];
-            continue;
-#endif
             const float ge = h.grad_scale * g[hh][e];
             const float mn = h.beta1 * m[hh][e] + h.one_minus_beta1 * ge;
             const float vn = h.beta2 * v[hh][e] + (h.one_minus_beta2 * ge) * ge;
@@ -446,7 +446,7 @@ __global__ __launch_bounds__(kWave) void concat_kernel(const ConcatArgs a)
     if (vec >= a.vec_per_shard) return;
     const u32x4 val = ld_stream(reinterpret_cast<const u32x4 *>(a.src[s]) + vec);
     u32x4 *dst = a.dst + (size_t)s * a.vec_per_shard + vec;
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(val) : "memory");
+    st_writethrough(dst, val);
 }
 
 // The same copy for the buckets of many layers in one launch (the post-step gather runs for all
@@ -468,8 +468,7 @@ __global__ __launch_bounds__(kWave) void concat_layers_kernel(const ConcatLayers
     const uint32_t vec = blockIdx.x * kWave + threadIdx.x;
     if (vec >= n) return;
     const u32x4 val = ld_stream(reinterpret_cast<const u32x4 *>(a.src[s]) + vec);
-    u32x4 *dst = a.dst[layer] + (size_t)k * n + vec;
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(val) : "memory");
+    st_writethrough(a.dst[layer] + (size_t)k * n + vec, val);
 }
 
 // The same copy for pieces of different lengths (a ZeRO-3 shard rebuilt from whole and partial
@@ -492,8 +491,7 @@ __global__ __launch_bounds__(kWave) void concat_ranges_kernel(const ConcatRanges
     const uint32_t vec = tile * kWave + threadIdx.x;
     if (vec >= a.nvec[s]) return;
     const u32x4 val = ld_stream(reinterpret_cast<const u32x4 *>(a.src[s]) + vec);
-    u32x4 *dst = a.dst + (size_t)a.dst_vec[s] + vec;
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(dst), "v"(val) : "memory");
+    st_writethrough(a.dst + (size_t)a.dst_vec[s] + vec, val);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -566,8 +564,7 @@ __global__ __launch_bounds__(kWave) void unpack_kernel(const UnpackArgs a)
 #pragma unroll
         for (int i = 0; i < U; ++i) {
             const uint32_t q = q0 + i * kWave + lane;
-            if (q < nbody)
-                asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(bdst + q), "v"(val[i]) : "memory");
+            if (q < nbody) st_writethrough(bdst + q, val[i]);
         }
     }
 }
@@ -623,11 +620,7 @@ static void launch_fused_variant(bool g32, bool o32, uint32_t R, const Seg &a, c
     const dim3 block(kWave);
     // The occupancy cap pays off only where every load is issued up front (compile-time R);
     // the run-time-R loop keeps two contributions in flight and needs the resident wavefronts.
-#ifdef HZP_TUNE      // tuning builds only: sweep the occupancy cap without recompiling
-    unsigned lds = getenv("HZP_FUSED_LDS") ? (unsigned)atoi(getenv("HZP_FUSED_LDS")) : kFusedLdsBytes;
-#else
-    unsigned lds = kFusedLdsBytes;
-#endif
+    const unsigned lds = kFusedLdsBytes;
 #define HZP_FUSED_CASE(RT, G, O) \
     hipLaunchKernelGGL((fused_adamw_kernel<RT, G, O, Seg, Wd>), grid, block, (RT) ? lds : 0u, stream, a, h, w)
     if (!g32 && !o32) {
@@ -658,6 +651,21 @@ static void launch_fused_variant(bool g32, bool o32, uint32_t R, const Seg &a, c
 #undef HZP_FUSED_CASE
 }
 
+// Most groups one launch of the fused update covers (about 150 M elements, 0.6-1.3 ms of work).
+// Workgroups go to the 8 XCDs round-robin, so each XCD owns a fixed eighth of the groups of a
+// launch; the XCDs do not run at exactly the same speed, and over a long launch they drift apart
+// (measured on MI355X: by 5-10 % of the grid after 3 ms), which spreads the addresses in flight and
+// leaves the slowest XCD to finish alone.  A launch boundary lines them up again for a few
+// microseconds: at R = 16 on 72 M-element shards, launches of 140-280 k groups stream 2-6 % faster
+// than one launch over everything, and shorter ones lose to the gaps between launches.
+constexpr uint32_t kMaxGroupsPerLaunch = 300000;
+
+// A run of one segment handled by one launch: elements [first, first + n) of segment `seg`.
+struct SegRun {
+    uint32_t seg;
+    uint64_t first, n;
+};
+
 template <class Seg>
 static hzp_status_t launch_fused_table(const hzp_plan_t *plan, bool use_wd, bool g32, bool o32, uint32_t R,
                                        const FusedSegment *segs, size_t nseg, const AdamScalars &h,
@@ -670,33 +678,45 @@ static hzp_status_t launch_fused_table(const hzp_plan_t *plan, bool use_wd, bool
     }
     const uint32_t per_seg = R + 4;
     const size_t cap = std::min<size_t>(Seg::kMaxSeg, Seg::kPtrCap / per_seg);
-    size_t s0 = 0;
-    while (s0 < nseg) {
+    const uint32_t gsz = g32 ? 4u : 2u, osz = o32 ? 4u : 2u;
+    constexpr uint64_t kGroupElems = 4ull * kGroupQuads;
+    // Cut the segments into runs of at most kMaxGroupsPerLaunch groups (a shard longer than that is
+    // covered by several launches), then fill launches with whole runs.
+    std::vector<SegRun> runs;
+    try {
+        for (size_t s = 0; s < nseg; ++s)
+            for (uint64_t first = 0; first < segs[s].n; first += kMaxGroupsPerLaunch * kGroupElems)
+                runs.push_back(SegRun{(uint32_t)s, first, std::min<uint64_t>(segs[s].n - first, kMaxGroupsPerLaunch * kGroupElems)});
+    } catch (const std::bad_alloc &) {
+        return fail(HZP_ERR_NOMEM, "hzp_adamw_shard: out of host memory");
+    }
+    size_t r0 = 0;
+    while (r0 < runs.size()) {
         Seg a{};
         WdLookup w{};
         uint32_t blocks = 0;
         uint32_t cnt = 0;
-        for (; s0 + cnt < nseg && cnt < cap; ++cnt) {
-            const FusedSegment &f = segs[s0 + cnt];
-            const uint32_t nquad = (uint32_t)(f.n / 4);
+        for (; r0 + cnt < runs.size() && cnt < cap; ++cnt) {
+            const SegRun &run = runs[r0 + cnt];
+            const FusedSegment &f = segs[run.seg];
+            const uint32_t nquad = (uint32_t)(run.n / 4);
             const uint32_t nb = (nquad + kGroupQuads - 1) / kGroupQuads;
-            if (blocks + nb < blocks || blocks + nb > 0x7FFFFFFFu) break;   // start another launch
+            if (cnt > 0 && blocks + nb > kMaxGroupsPerLaunch) break;    // start another launch
             blocks += nb;
             a.blk_end[cnt] = blocks;
             a.nquad[cnt] = nquad;
             const void **sp = a.ptr + (size_t)cnt * per_seg;
-            for (uint32_t r = 0; r < R; ++r) sp[r] = f.grads[r];
-            sp[R] = f.master;
-            sp[R + 1] = f.m;
-            sp[R + 2] = f.v;
-            sp[R + 3] = f.out;
+            for (uint32_t r = 0; r < R; ++r) sp[r] = static_cast<const char *>(f.grads[r]) + run.first * gsz;
+            sp[R] = f.master + run.first;
+            sp[R + 1] = f.m + run.first;
+            sp[R + 2] = f.v + run.first;
+            sp[R + 3] = f.out ? static_cast<char *>(f.out) + run.first * osz : nullptr;
             if constexpr (std::is_same<Seg, SegTableNarrow>::value) {
                 w.first_slot[cnt] = f.first_slot;
                 w.n_tensors[cnt] = f.n_tensors;
-                w.shard_begin[cnt] = f.shard_begin;
+                w.shard_begin[cnt] = f.shard_begin + run.first;
             }
         }
-        if (cnt == 0) return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: shard too large for one launch");
         a.nseg = cnt;
         a.R = R;
         // Two-dimensional grid unless the segments differ so much in length that more than an
@@ -707,10 +727,7 @@ static hzp_status_t launch_fused_table(const hzp_plan_t *plan, bool use_wd, bool
             max_groups = std::max(max_groups, groups);
         }
         dim3 grid(blocks);
-        bool two_d = (uint64_t)max_groups * cnt - blocks <= blocks / 8 && cnt <= 65535;
-#ifdef HZP_TUNE
-        if (getenv("HZP_FUSED_2D")) two_d = two_d && atoi(getenv("HZP_FUSED_2D")) != 0;
-#endif
+        const bool two_d = (uint64_t)max_groups * cnt - blocks <= blocks / 8 && cnt <= 65535;
         if (two_d) {
             for (uint32_t c = cnt; c-- > 0;) a.blk_end[c] -= c ? a.blk_end[c - 1] : 0u;
             a.grid2d = 1;
@@ -727,7 +744,7 @@ static hzp_status_t launch_fused_table(const hzp_plan_t *plan, bool use_wd, bool
             hzp_status_t st = check_launch("hzp_adamw_shard");
             if (st != HZP_OK) return st;
         }
-        s0 += cnt;
+        r0 += cnt;
     }
     return HZP_OK;
 }
@@ -1001,6 +1018,24 @@ hzp_status_t device_tables(const hzp_plan_t *plan, const DeviceTables **out)
     *out = &plan->dev.back();
     return HZP_OK;
 }
+
+}  // namespace hzp
+
+extern "C" hzp_status_t hzp_plan_prepare(const hzp_plan_t *plan, hipStream_t stream)
+{
+    if (!plan) return hzp::fail(HZP_ERR_INVALID_ARG, "hzp_plan_prepare: NULL plan");
+    const hzp::DeviceTables *tab = nullptr;
+    hzp_status_t st = hzp::device_tables(plan, &tab);       // allocates and copies (blocking) on first use
+    if (st != HZP_OK) return st;
+    // The copies above were blocking host-to-device copies on the null stream; a stream created
+    // as non-blocking is not ordered behind them by itself, so wait for them once here.
+    hipError_t e = hipStreamSynchronize(stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) return hzp::fail(HZP_ERR_HIP, "hzp_plan_prepare: %s", hipGetErrorString(e));
+    return HZP_OK;
+}
+
+namespace hzp {
 
 void free_device_tables(hzp_plan_t *plan)
 {

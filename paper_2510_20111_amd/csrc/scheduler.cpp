@@ -68,7 +68,7 @@ struct Cmd {
     int level = 0, accumulate = 0;
     float scale = 1.0f;
     float *out = nullptr;
-    hipEvent_t after = nullptr;     // recorded on the producer's stream at submission
+    hipEvent_t after = nullptr;     // both kinds: recorded on the producer's stream at submission
     std::vector<const void *> ptrs; // both kinds
 };
 
@@ -77,6 +77,7 @@ struct Cmd {
 struct hzp_sched {
     const hzp_plan_t *plan = nullptr;
     uint32_t cls = 0, max_live = 0, queue_capacity = 0;
+    bool copy_engine = false;                   // bucket gathers as device-to-device copies, not kernels
     int device = 0;
     uint64_t pool_bytes = 0;
     uint64_t uniform_bytes = 0;                 // non-zero: every region takes this much (equal slots)
@@ -179,20 +180,32 @@ void worker_main(hzp_sched *s)
         }
         if (cmd.kind == Cmd::STOP) break;
         if (cmd.kind == Cmd::PREFETCH) {
-            hipError_t e = hipSuccess;
+            // The shards exist once the producer's work enqueued before the prefetch has run.
+            hipError_t e = hipStreamWaitEvent(s->gather_stream, cmd.after, 0);
             for (hipEvent_t ev : cmd.wait)          // earlier users of this part of the ring
                 if (e == hipSuccess) e = hipStreamWaitEvent(s->gather_stream, ev, 0);
             hzp_status_t st = HZP_OK;
             if (e == hipSuccess) {
-                void *dst = s->pool + cmd.off;
-                st = cmd.is_tensor
-                         ? hzp_gather_tensor(s->plan, cmd.id, cmd.ptrs.data(), (uint32_t)cmd.ptrs.size(), dst,
-                                             s->gather_stream)
-                         : hzp_gather_layer(s->plan, cmd.id, s->cls, 3, cmd.ptrs.data(), (uint32_t)cmd.ptrs.size(),
-                                            dst, nullptr, s->gather_stream);
+                char *dst = s->pool + cmd.off;
+                if (cmd.is_tensor) {
+                    st = hzp_gather_tensor(s->plan, cmd.id, cmd.ptrs.data(), (uint32_t)cmd.ptrs.size(), dst,
+                                           s->gather_stream);
+                } else if (s->copy_engine) {
+                    // One device-to-device copy per shard: the copy engines move the data, no
+                    // workgroup is launched, so a compute kernel that fills the CUs is not disturbed.
+                    const BucketRec *b = find_bucket(s->plan, cmd.id, s->cls);
+                    const size_t bytes = (size_t)b->S3 * (s->cls == HZP_CLASS_F32 ? 4 : 2);
+                    for (size_t j = 0; j < cmd.ptrs.size() && e == hipSuccess; ++j)
+                        e = hipMemcpyAsync(dst + j * bytes, cmd.ptrs[j], bytes, hipMemcpyDeviceToDevice,
+                                           s->gather_stream);
+                } else {
+                    st = hzp_gather_layer(s->plan, cmd.id, s->cls, 3, cmd.ptrs.data(), (uint32_t)cmd.ptrs.size(),
+                                          dst, nullptr, s->gather_stream);
+                }
             }
             if (e == hipSuccess && st == HZP_OK) e = hipEventRecord(cmd.ready, s->gather_stream);
             std::lock_guard<std::mutex> lock(s->mu);
+            s->spare_events.push_back(cmd.after);
             for (hipEvent_t ev : cmd.wait) s->spare_events.push_back(ev);   // their waits are enqueued: reusable
             if (e != hipSuccess || st != HZP_OK) {
                 s->set_failed(st != HZP_OK ? st : HZP_ERR_HIP, st != HZP_OK ? hzp_last_error() : hipGetErrorString(e));
@@ -260,7 +273,7 @@ void sweep_freed(hzp_sched *s)
 
 // Common part of the two prefetch calls; `ptrs` have been validated.
 hzp_status_t prefetch_region(hzp_sched *s, const char *who, uint64_t key, bool is_tensor, uint32_t id, uint64_t payload,
-                             const void *const *ptrs, uint32_t n)
+                             const void *const *ptrs, uint32_t n, hipStream_t producer)
 {
     std::unique_lock<std::mutex> lock(s->mu);
     if (s->failed != HZP_OK) return fail(s->failed, "scheduler failed earlier: %s", s->fail_text);
@@ -281,6 +294,16 @@ hzp_status_t prefetch_region(hzp_sched *s, const char *who, uint64_t key, bool i
     cmd.ptrs.assign(ptrs, ptrs + n);
     hipError_t e = take_event(s, &cmd.ready);
     if (e != hipSuccess) return hip_fail(s, who, e);
+    e = take_event(s, &cmd.after);
+    if (e == hipSuccess) {
+        e = hipEventRecord(cmd.after, producer);
+        if (e != hipSuccess) s->spare_events.push_back(cmd.after);
+    }
+    if (e != hipSuccess) {
+        s->spare_events.push_back(cmd.ready);
+        return hip_fail(s, who, e);
+    }
+    const hipEvent_t after = cmd.after;
     // The gather must run after the last use of everything that lay in [off, off+bytes) before.
     std::vector<FreedRegion> taken;
     size_t kept = 0;
@@ -306,6 +329,7 @@ hzp_status_t prefetch_region(hzp_sched *s, const char *who, uint64_t key, bool i
     if (st != HZP_OK) {             // not queued: undo
         s->live.pop_back();
         s->spare_events.push_back(a.ready);
+        s->spare_events.push_back(after);
         s->freed.insert(s->freed.end(), taken.begin(), taken.end());
         return st;
     }
@@ -384,6 +408,7 @@ extern "C" hzp_status_t hzp_sched_create(const hzp_plan_t *plan, const hzp_sched
         return fail(HZP_ERR_INVALID_ARG, "hzp_sched_create: needs at least one pool slot and one queue entry");
     if (d->pool_bytes % 256 != 0)
         return fail(HZP_ERR_INVALID_ARG, "hzp_sched_create: pool_bytes must be a multiple of 256");
+    if (d->copy_engine > 1) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_create: copy_engine is 0 or 1");
     uint64_t max_p = 0;
     for (const BucketRec &b : plan->buckets)
         if (b.cls == d->cls) max_p = std::max(max_p, b.P);
@@ -395,10 +420,18 @@ extern "C" hzp_status_t hzp_sched_create(const hzp_plan_t *plan, const hzp_sched
     s->cls = d->cls;
     s->max_live = d->gather_slots;
     s->queue_capacity = d->queue_capacity;
+    s->copy_engine = d->copy_engine != 0;
     // Without an explicit size the ring is cut into equal slots of the largest bucket, so that any
     // `gather_slots` regions fit whatever their sizes; with one, a region takes its own size.
     s->pool_bytes = d->pool_bytes ? d->pool_bytes : slot_bytes * d->gather_slots;
     s->uniform_bytes = d->pool_bytes ? 0 : slot_bytes;
+    // The plan's device tables are made here, so that no gather launched by the background thread
+    // has to allocate or block.
+    hzp_status_t pst = hzp_plan_prepare(plan, nullptr);
+    if (pst != HZP_OK) {
+        delete s;
+        return pst;
+    }
     hipError_t e = hipGetDevice(&s->device);
     // One allocation for the whole pool: contiguous, never freed or grown until destroy.
     if (e == hipSuccess) e = hipMalloc((void **)&s->pool, s->pool_bytes);
@@ -448,7 +481,7 @@ extern "C" void hzp_sched_destroy(hzp_sched_t *s)
 }
 
 extern "C" hzp_status_t hzp_sched_prefetch(hzp_sched_t *s, uint32_t layer, const void *const *shard_ptrs,
-                                           uint32_t n_shards)
+                                           uint32_t n_shards, hipStream_t producer)
 {
     if (!s || !shard_ptrs) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_prefetch: NULL argument");
     const BucketRec *b = find_bucket(s->plan, layer, s->cls);
@@ -463,11 +496,33 @@ extern "C" hzp_status_t hzp_sched_prefetch(hzp_sched_t *s, uint32_t layer, const
             return fail(HZP_ERR_ALIGN, "hzp_sched_prefetch: shard %u is not 16-byte aligned", i);
     }
     return prefetch_region(s, "hzp_sched_prefetch: layer", layer, false, layer,
-                           b->P * (s->cls == HZP_CLASS_F32 ? 4 : 2), shard_ptrs, n_shards);
+                           b->P * (s->cls == HZP_CLASS_F32 ? 4 : 2), shard_ptrs, n_shards, producer);
+}
+
+extern "C" hzp_status_t hzp_sched_prefetch_ahead(hzp_sched_t *s, uint32_t first_layer, uint32_t n_layers,
+                                                 const void *const *shard_ptrs, uint32_t n_shards,
+                                                 hipStream_t producer, uint32_t *issued)
+{
+    if (!s || !shard_ptrs || !issued) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_prefetch_ahead: NULL argument");
+    *issued = 0;
+    if ((uint64_t)first_layer + n_layers > s->plan->n_layers)
+        return fail(HZP_ERR_RANGE, "hzp_sched_prefetch_ahead: layers [%u, %u + %u) of %u", first_layer, first_layer,
+                    n_layers, s->plan->n_layers);
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        if (!find_bucket(s->plan, first_layer + l, s->cls)) {      // no bucket of the class: nothing to gather
+            ++*issued;
+            continue;
+        }
+        hzp_status_t st = hzp_sched_prefetch(s, first_layer + l, shard_ptrs + (size_t)l * n_shards, n_shards, producer);
+        if (st == HZP_ERR_NOMEM) return HZP_OK;     // the pool is full: as far ahead as the memory allows
+        if (st != HZP_OK) return st;
+        ++*issued;
+    }
+    return HZP_OK;
 }
 
 extern "C" hzp_status_t hzp_sched_prefetch_tensor(hzp_sched_t *s, uint32_t tensor_id, const void *const *shard_ptrs,
-                                                  uint32_t n_shards)
+                                                  uint32_t n_shards, hipStream_t producer)
 {
     if (!s || !shard_ptrs) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_prefetch_tensor: NULL argument");
     if (tensor_id >= s->plan->tensors.size())
@@ -489,7 +544,7 @@ extern "C" hzp_status_t hzp_sched_prefetch_tensor(hzp_sched_t *s, uint32_t tenso
                         (unsigned long long)j);
     }
     return prefetch_region(s, "hzp_sched_prefetch_tensor: tensor", kTensorKey | tensor_id, true, tensor_id,
-                           t.numel * (s->cls == HZP_CLASS_F32 ? 4 : 2), shard_ptrs, n_shards);
+                           t.numel * (s->cls == HZP_CLASS_F32 ? 4 : 2), shard_ptrs, n_shards, producer);
 }
 
 extern "C" hzp_status_t hzp_sched_acquire(hzp_sched_t *s, uint32_t layer, hipStream_t consumer, void **bucket)

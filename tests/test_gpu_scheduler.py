@@ -10,7 +10,7 @@ import paper_2510_20111_amd as hzp
 from oracle import numeric as on
 from oracle import planner as op
 
-from gpu_util import DEV, oracle_plan, to_dev, to_host
+from gpu_util import DEV, assert_bf16_within_one_ulp, oracle_plan, to_dev, to_host
 from test_gpu_parity import lib_plan, say
 
 pytestmark = pytest.mark.gpu
@@ -169,23 +169,11 @@ def test_hungry_reduce_after_the_producer_and_join():
     sched.destroy()
 
 
-def _ring_model(cap, live, nbytes):
-    """Where the next region of a ring goes: live = [(off, bytes)] oldest first.  None if no room."""
-    if nbytes > cap:
-        return None
-    if not live:
-        return 0
-    tail, head = live[0][0], live[-1][0] + live[-1][1]
-    if head > tail:
-        if head + nbytes <= cap:
-            return head
-        return 0 if nbytes <= tail else None
-    return head if head + nbytes <= tail else None
-
-
 def test_ring_pool_with_layers_of_different_sizes():
-    """Buckets of very different sizes move through a ring that is smaller than three of the largest:
-    every bucket arrives intact, regions follow the ring arithmetic, and space is lost only at wraps."""
+    """Buckets of very different sizes move through a ring that is smaller than three of the largest.
+    Checked without a model of the ring's arithmetic: every bucket arrives intact; regions that are
+    live at the same time never overlap; all regions lie inside one window of pool_bytes; the live
+    bytes never exceed the pool; a full pool refuses with NOMEM and an empty one always accepts."""
     say("scheduler: ring pool, ragged layers")
     rng = np.random.default_rng(60)
     n_layers = 14
@@ -198,48 +186,203 @@ def test_ring_pool_with_layers_of_different_sizes():
         bucket = rng.integers(0, 1 << 16, size=b["P"], dtype=np.uint64).astype(np.uint16)
         shards.append([np.ascontiguousarray(bucket[j * b["S3"]:(j + 1) * b["S3"]]) for j in range(4)])
         dshards.append([to_dev(s) for s in shards[-1]])
-    sizes = [(2 * b["P"] + 255) // 256 * 256 for b in oplan["buckets"]]
-    cap = 2 * max(sizes) + 4096
-    sched = hzp.Sched(plan, gather_slots=4, queue_capacity=8, pool_bytes=cap)
+    sizes = [2 * b["P"] for b in oplan["buckets"]]
+    cap = 2 * ((max(sizes) + 255) // 256 * 256) + 4096
+    slots = 4
+    sched = hzp.Sched(plan, gather_slots=slots, queue_capacity=8, pool_bytes=cap)
     consumer = torch.cuda.Stream()
     outs = [torch.zeros(b["P"], dtype=torch.int16, device=DEV) for b in oplan["buckets"]]
     torch.cuda.synchronize()
-    live, base, nxt, skipped = [], None, 0, 0
+    pending, held = [], []          # prefetched but not acquired; acquired: (layer, address, bytes)
+    seen, nxt, refusals = [], 0, 0
 
-    def try_prefetch():
-        nonlocal nxt, skipped
-        while nxt < n_layers and len(live) < 4:
-            off = _ring_model(cap, [(o, n) for _, o, n in live], sizes[nxt])
-            if off is None:
-                with pytest.raises(hzp.HzpError) as e:
-                    sched.prefetch(nxt, dshards[nxt])
-                assert e.value.status == hzp.HZP_ERR_NOMEM
+    def prefetch_all_it_takes():
+        nonlocal nxt, refusals
+        while nxt < n_layers:
+            try:
+                sched.prefetch(nxt, dshards[nxt], consumer)
+            except hzp.HzpError as e:
+                assert e.status == hzp.HZP_ERR_NOMEM
+                assert pending or held, "an empty pool refused a region that fits"
+                refusals += 1
                 return
-            if live and off == 0 and live[-1][1] + live[-1][2] > live[0][1]:
-                skipped += cap - (live[-1][1] + live[-1][2])
-            sched.prefetch(nxt, dshards[nxt])
-            live.append((nxt, off, sizes[nxt]))
+            pending.append(nxt)
             nxt += 1
+            assert len(pending) + len(held) <= slots
 
-    try_prefetch()
-    for l in range(n_layers):
-        assert live and live[0][0] == l
-        ptr = sched.acquire(l, consumer)
-        base = ptr - live[0][1] if base is None else base
-        assert ptr - base == live[0][1], (l, ptr - base, live[0])
-        with torch.cuda.stream(consumer):
-            outs[l].copy_(view16(ptr, outs[l].numel()))
-        sched.release(l, consumer)
-        live.pop(0)
-        try_prefetch()
+    prefetch_all_it_takes()
+    while pending or held:
+        # acquire everything that is prefetched: all of these regions are live at the same time
+        while pending:
+            l = pending.pop(0)
+            ptr = sched.acquire(l, consumer)
+            held.append((l, ptr, sizes[l]))
+            seen.append((ptr, sizes[l]))
+        for i, (la, pa, na) in enumerate(held):
+            for lb, pb, nb in held[i + 1:]:
+                assert pa + na <= pb or pb + nb <= pa, "regions of layers %d and %d overlap" % (la, lb)
+        assert sum(n for _, _, n in held) <= cap
+        lo, hi = min(p for p, _ in seen), max(p + n for p, n in seen)
+        assert hi - lo <= cap, "regions span more than the pool"
+        # use and give back the oldest one (two at times, so that the number of live regions varies)
+        for _ in range(2 if len(held) > 2 and held[0][0] % 3 == 0 else 1):
+            l, ptr, _ = held.pop(0)
+            with torch.cuda.stream(consumer):
+                outs[l].copy_(view16(ptr, outs[l].numel()))
+            sched.release(l, consumer)
+        prefetch_all_it_takes()
     consumer.synchronize()
     sched.drain()
     for l in range(n_layers):
         assert np.array_equal(to_host(outs[l], np.uint16), on.gather_concat(shards[l])), l
     st = sched.stats()
     assert st.pool_bytes == cap and st.gathers_issued == n_layers
-    assert st.peak_live_bytes <= cap and 2 <= st.peak_live_slots <= 4
-    assert st.wrap_skipped_bytes == skipped and skipped > 0
+    assert st.peak_live_bytes <= cap and 2 <= st.peak_live_slots <= slots
+    assert refusals > 0                                     # the pool did fill up
+    # space is lost only where a region does not fit before the end of the buffer: less than one
+    # region each time, and not more often than regions were placed
+    assert 0 < st.wrap_skipped_bytes < n_layers * max(sizes)
+    sched.destroy()
+
+
+def test_prefetch_right_behind_the_update_without_a_host_wait():
+    """Section 4.1.2: the optimizer step writes the new bf16 parameters into the rank's piece of the
+    ZeRO-3 shard and the next step's prefetch is issued at once.  The update sits behind a long
+    kernel on the compute stream when the prefetch is queued; the gather must wait for it through the
+    producer's event alone (no host synchronisation anywhere)."""
+    say("scheduler: prefetch ordered behind the producer stream")
+    desc = dict(tensors_per_layer=[2, 2], tensor_numel=[50000, 30000, 70000, 10000])
+    z3, z1, R = 2, 4, 2
+    oplan, plan = oracle_plan(desc, 8, z3, z1), lib_plan(desc, 8, z3, z1)
+    rank = 3                                    # j = 1, k = 1
+    j, k, i = plan.rank(rank)
+    hp = hzp_inputs.ADAMW
+    hy = hzp.adamw_hyper(hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"], 1.0 / R, 1)
+    rng = np.random.default_rng(70)
+    compute = torch.cuda.Stream()
+    sched = hzp.Sched(plan, gather_slots=2, queue_capacity=8)
+    busy = torch.randn(4096, 4096, device=DEV)
+    host, dev = [], []
+    for layer, b in enumerate(oplan["buckets"]):
+        beg, n = op.shard_range(oplan, b, 1, rank)
+        g = [hzp_inputs.to_bf16_bits((rng.standard_normal(n) * 1e-3).astype(np.float32)) for _ in range(R)]
+        p = (rng.standard_normal(n) * 0.02).astype(np.float32)
+        other = [rng.integers(0, 1 << 16, size=b["S3"], dtype=np.uint64).astype(np.uint16) for _ in range(z3)]
+        dsh = [to_dev(o) for o in other]            # shard j holds stale values where the update will write
+        host.append(dict(g=g, p=p, other=other, S1=b["S1"], S3=b["S3"], P=b["P"]))
+        dev.append(dict(g=[to_dev(x) for x in g], p=to_dev(p), m=torch.zeros(n, device=DEV), v=torch.zeros(n, device=DEV),
+                        shards=dsh, out=dsh[j][k * b["S1"]:(k + 1) * b["S1"]]))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(compute):
+        for _ in range(30):
+            busy = busy @ busy * 1e-3           # the update below is queued behind this
+    hzp.hzp_adamw_shard(plan, 0, 2, 0, rank, hy, [x for d in dev for x in d["g"]], R, [d["p"] for d in dev],
+                        [d["m"] for d in dev], [d["v"] for d in dev], [d["out"] for d in dev], stream=compute)
+    ptrs = [x for d in dev for x in d["shards"]]
+    assert sched.prefetch_ahead(0, 2, ptrs, z3, compute) == 2       # queued at once, ordered by the event
+    got = []
+    for layer in range(2):
+        ptr = sched.acquire(layer, compute)
+        with torch.cuda.stream(compute):
+            got.append(view16(ptr, host[layer]["P"]).clone())
+        sched.release(layer, compute)
+    compute.synchronize()
+    sched.drain()
+    for layer, h in enumerate(host):
+        want16 = on.adamw(on.reduce(h["g"], scale=1.0 / R), h["p"].copy(), np.zeros_like(h["p"]), np.zeros_like(h["p"]),
+                          step=1, **hp)
+        shards = [o.copy() for o in h["other"]]
+        bucket = to_host(got[layer], np.uint16)
+        mine = bucket[j * h["S3"] + k * h["S1"]:j * h["S3"] + (k + 1) * h["S1"]]
+        # the piece written by the update: the oracle's cast parameters within one bf16 ulp
+        big = np.abs(h["p"]) > 1e-4         # away from zero one bf16 ulp is far wider than the fp32 tolerance
+        assert_bf16_within_one_ulp(mine[big], want16[big], "layer %d: piece written by the update" % layer)
+        assert not np.array_equal(mine, shards[j][k * h["S1"]:(k + 1) * h["S1"]])   # not the stale values
+        shards[j][k * h["S1"]:(k + 1) * h["S1"]] = mine
+        assert np.array_equal(bucket, on.gather_concat(shards)), layer
+    sched.destroy()
+
+
+def test_prefetch_ahead_fills_the_pool_and_the_turn_from_forward_to_backward():
+    """Section 4.1.2: prefetch as far ahead as the memory allows; at the end of the forward pass the
+    last layer's parameters, released after their use, are gathered again for the backward pass."""
+    say("scheduler: prefetch ahead and the forward/backward turn")
+    n_layers = 6
+    oplan, plan, shards = _layers(n_layers, 54)
+    dshards = [[to_dev(s) for s in layer] for layer in shards]
+    flat = [x for layer in dshards for x in layer]
+    slots = 3
+    sched = hzp.Sched(plan, gather_slots=slots, queue_capacity=8)
+    consumer = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    seen = []
+
+    def use(l):
+        ptr = sched.acquire(l, consumer)
+        with torch.cuda.stream(consumer):
+            seen.append((l, view16(ptr, oplan["buckets"][l]["P"]).clone()))
+        sched.release(l, consumer)
+
+    # forward: layers 0..5, the pool holds three
+    nxt = sched.prefetch_ahead(0, n_layers, flat, 4, consumer)
+    assert nxt == slots
+    assert sched.prefetch_ahead(nxt, n_layers - nxt, flat[4 * nxt:], 4, consumer) == 0      # full: nothing more, no error
+    for l in range(n_layers):
+        use(l)
+        if nxt < n_layers:
+            nxt += sched.prefetch_ahead(nxt, 1, flat[4 * nxt:], 4, consumer)
+    assert nxt == n_layers
+    # the turn: layer 5 was released; backward needs 5, 4, 3, ... again
+    order = list(range(n_layers - 1, -1, -1))
+    issued = 0
+    for l in order[:slots]:
+        sched.prefetch(l, dshards[l], consumer)
+        issued += 1
+    for idx, l in enumerate(order):
+        use(l)
+        if issued < n_layers:
+            sched.prefetch(order[issued], dshards[order[issued]], consumer)
+            issued += 1
+    consumer.synchronize()
+    sched.drain()
+    assert [l for l, _ in seen] == list(range(n_layers)) + order
+    for l, t in seen:
+        assert np.array_equal(to_host(t, np.uint16), on.gather_concat(shards[l])), l
+    st = sched.stats()
+    assert st.gathers_issued == 2 * n_layers and st.peak_live_slots == slots
+    with pytest.raises(hzp.HzpError) as e:
+        sched.prefetch_ahead(4, 5, flat, 4, consumer)
+    assert e.value.status == hzp.HZP_ERR_RANGE
+    sched.destroy()
+
+
+def test_bucket_gathers_through_the_copy_engines():
+    """copy_engine = 1: the same pipeline with device-to-device copies in place of the copy kernel."""
+    say("scheduler: copy-engine gathers")
+    n_layers = 7
+    oplan, plan, shards = _layers(n_layers, 55)
+    dshards = [[to_dev(s) for s in layer] for layer in shards]
+    sched = hzp.Sched(plan, gather_slots=2, queue_capacity=4, copy_engine=True)
+    consumer = torch.cuda.Stream()
+    busy = torch.randn(2048, 2048, device=DEV)
+    outs = [torch.zeros(oplan["buckets"][l]["P"], dtype=torch.int16, device=DEV) for l in range(n_layers)]
+    torch.cuda.synchronize()
+    sched.prefetch(0, dshards[0], consumer)
+    sched.prefetch(1, dshards[1], consumer)
+    for l in range(n_layers):
+        with torch.cuda.stream(consumer):
+            busy = busy @ busy * 1e-3
+        ptr = sched.acquire(l, consumer)
+        with torch.cuda.stream(consumer):
+            outs[l].copy_(view16(ptr, outs[l].numel()))
+        sched.release(l, consumer)
+        if l + 2 < n_layers:
+            sched.prefetch(l + 2, dshards[l + 2], consumer)
+    consumer.synchronize()
+    sched.drain()
+    for l in range(n_layers):
+        assert np.array_equal(to_host(outs[l], np.uint16), on.gather_concat(shards[l])), l
+    assert sched.stats().gathers_issued == n_layers
     sched.destroy()
 
 
