@@ -8,6 +8,11 @@ A step is one pass of the whole path over one rank's share of a model-shaped sta
   3. level-3 gather: Z3 parameter shards -> the full padded layer bucket, per bucket
 The layout plan is built once before the loop (it is static).  All inputs are synthetic, seeded
 and resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+The headline workload is the largest of the five that fits one GPU: the full MoE layer set (24
+layers, R = 16, about 200 GB resident).  After it, the same step is timed on the other four
+workloads (fewer repetitions) and reported under "configs": one {fused, gather1, gather3} roofline
+triple per workload.  `--config N` times one workload only.
 """
 import argparse
 import json
@@ -27,14 +32,15 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1, help="workload index 0..4 (1 = 7B-class dense)")
+    ap.add_argument("--config", type=int, default=-1,
+                    help="time only workload 0..4 (tiny, dense7b, dense70b, moe, irregular); default: headline on "
+                         "moe, then the other four under \"configs\"")
+    ap.add_argument("--other-steps", type=int, default=10, help="timed steps of each non-headline workload")
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--separate-allocations", action="store_true",
                     help="give every slice its own allocation instead of per-kind arenas (layout experiment)")
-    ap.add_argument("--one-allocation", type=int, default=-1, metavar="SKEW",
-                    help="carve every arena from one allocation, consecutive arenas SKEW bytes further apart (experiment)")
     ap.add_argument("--gather1-per-layer", action="store_true",
                     help="issue the level-1 gather as one call per layer instead of one call for all layers")
     ap.add_argument("--phases", default="fused,gather1,gather3",
@@ -53,8 +59,13 @@ class Workload:
     bucket's slice is the plan's `base` divided by the group size.  `separate=True` gives every
     slice its own allocation instead (a layout experiment: it streams about 4 % slower)."""
 
-    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False, one_alloc_skew=-1):
+    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False, l3_pool=0):
+        """l3_pool > 0: the level-3 gather streams through a rotating pool (the cyclic buffers of
+        Section 4.2): the received ZeRO-3 shards of only `l3_pool` layers and two destination buckets
+        are resident, layer l using slot l % l3_pool and bucket l % 2.  For layer streams whose full
+        buckets (2 bytes x P x layers) do not fit beside the rest."""
         self.cfg, self.rank = cfg, rank
+        self.l3_pool = l3_pool
         dev = "cuda:0"
         tpl = cfg["tensors_per_layer"][:n_layers]
         numel = cfg["tensor_numel"][:sum(tpl)]
@@ -69,23 +80,10 @@ class Workload:
         j, k, i = self.plan.rank(rank)
         bf16, f32 = torch.bfloat16, torch.float32
         arenas = {}
-        up = lambda b: (b + (2 << 20) - 1) // (2 << 20) * (2 << 20) + max(one_alloc_skew, 0)
-        self.one_alloc_bytes = (self.R * up(2 * self.s1_total) + 3 * up(4 * self.s1_total) + self.K * up(2 * self.s1_total)
-                                + (self.z3 + 1) * up(2 * self.s3_total) + up(2 * self.p_total) + (4 << 20))
-
-        big = {"buf": None, "off": 0}
 
         def arena(name, total, dtype):
             if name not in arenas:
-                if one_alloc_skew >= 0:
-                    if big["buf"] is None:
-                        big["buf"] = torch.empty(self.one_alloc_bytes, dtype=torch.uint8, device=dev)
-                    nbytes = total * (2 if dtype == bf16 else 4)
-                    arenas[name] = big["buf"][big["off"]:big["off"] + nbytes].view(dtype)
-                    big["off"] += (nbytes + (2 << 20) - 1) // (2 << 20) * (2 << 20) + one_alloc_skew
-                    assert big["off"] <= self.one_alloc_bytes
-                else:
-                    arenas[name] = torch.empty(total, dtype=dtype, device=dev)
+                arenas[name] = torch.empty(total, dtype=dtype, device=dev)
             return arenas[name]
 
         def piece(name, total, dtype, begin, n, fill=None):
@@ -124,9 +122,21 @@ class Workload:
                       for kk in range(self.K)]
             shard3 = piece("s3", self.s3_total, bf16, o3, b.s3).zero_()
             # level 3: this rank's shard is j; the other Z3-1 shards are "received"
-            shards = [shard3 if jj == j else piece("recv3_%d" % jj, self.s3_total, bf16, o3, b.s3).normal_()
-                      for jj in range(self.z3)]
-            bucket = piece("bucket", self.p_total, bf16, b.base, b.padded)
+            if l3_pool:
+                slot = l % l3_pool
+                s3_max, p_max = max(x.s3 for x in self.buckets), max(x.padded for x in self.buckets)
+                fresh = l < l3_pool
+                shards = [shard3 if jj == j else piece("recv3_%d" % jj, l3_pool * s3_max, bf16, slot * s3_max, b.s3)
+                          for jj in range(self.z3)]
+                if fresh:
+                    for jj in range(self.z3):
+                        if jj != j:
+                            shards[jj].normal_()
+                bucket = piece("bucket", 2 * p_max, bf16, (l % 2) * p_max, b.padded)
+            else:
+                shards = [shard3 if jj == j else piece("recv3_%d" % jj, self.s3_total, bf16, o3, b.s3).normal_()
+                          for jj in range(self.z3)]
+                bucket = piece("bucket", self.p_total, bf16, b.base, b.padded)
             self.keep.append((grads, p, m, v, out, owners, shard3, shards, bucket))
             g_ptrs += grads
             p_ptrs.append(p); m_ptrs.append(m); v_ptrs.append(v); o_ptrs.append(out)
@@ -313,20 +323,21 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
 
         def overlapped():
             for l in range(min(depth, n)):
-                sched.prefetch(l, w.l3_args[l][1])
+                sched.prefetch(l, w.l3_args[l][1], s)
             for l in range(n):
                 sched.acquire(l, s)
                 compute(l)
                 sched.release(l, s)
                 if l + depth < n:
-                    sched.prefetch(l + depth, w.l3_args[l + depth][1])
+                    sched.prefetch(l + depth, w.l3_args[l + depth][1], s)
             sched.join(s)
 
         t_compute, t_serial, t_async = timed(compute_only), timed(serial), timed(overlapped)
         sched.drain()
         st = sched.stats()
         out["cases"].append({
-            "compute": kind, "compute_only_ms": round(t_compute, 3),
+            "compute": kind,
+            "compute_only_ms": round(t_compute, 3),
             "serial_ms": round(t_serial, 3), "scheduled_ms": round(t_async, 3),
             "gather_time_hidden": round((t_serial - t_async) / t_gather, 3),
             "acquire_host_wait_us_per_layer": round(st.acquire_host_wait_us / max(1, st.gathers_issued), 2)})
@@ -355,7 +366,7 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
     def by_parameter():
         for l in range(min(depth, n)):
             for t in range(first[l], first[l + 1]):
-                sched.prefetch_tensor(t, needed[t])
+                sched.prefetch_tensor(t, needed[t], s)
         for l in range(n):
             for t in range(first[l], first[l + 1]):
                 sched.acquire_tensor(t, s)
@@ -364,7 +375,7 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
                 sched.release_tensor(t, s)
             if l + depth < n:
                 for t in range(first[l + depth], first[l + depth + 1]):
-                    sched.prefetch_tensor(t, needed[t])
+                    sched.prefetch_tensor(t, needed[t], s)
         sched.join(s)
 
     t_param = timed(by_parameter)
@@ -491,7 +502,9 @@ def cpu_baseline(w, torch, np):
 
 
 def read_traffic(kernel_key):
-    """HBM bytes per launch of a kernel as measured with rocprofv3 counters (committed summary)."""
+    """HBM bytes per launch of a kernel as measured with rocprofv3 counters: the committed summary
+    profiles/traffic_bytes_per_launch.txt, written from the FETCH_SIZE / WRITE_SIZE runs named there.
+    Returns None when the file has no line for the key (the key is printed beside it either way)."""
     path = os.path.join(ROOT, "profiles", "traffic_bytes_per_launch.txt")
     try:
         with open(path) as f:
@@ -504,44 +517,58 @@ def read_traffic(kernel_key):
     return None
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build covers the one-GPU share of the path only; replicas are buffers in one "
-              "GPU's HBM and no collective is issued, so --gpus must be 1 (got %d)" % args.gpus,
-              file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
+FUSED_MAX_GROUPS = 300000       # groups of 512 elements one launch of the fused update covers at most
 
-    import hzp_inputs
-    import paper_2510_20111_amd as hzp
 
-    torch.cuda.set_device(0)
-    cfg = hzp_inputs.config(args.config)
-    n_layers = len(cfg["tensors_per_layer"]) if args.layers <= 0 else min(args.layers, len(cfg["tensors_per_layer"]))
+def fused_launch_count(w):
+    """Launches one hzp_adamw_shard call over all buckets makes: a launch takes whole runs (a bucket's
+    shard, cut at FUSED_MAX_GROUPS groups) while they fit FUSED_MAX_GROUPS groups and the kernel's
+    segment table (34 segments, 408 pointers of R + 4 per segment)."""
+    cap = min(34, 408 // (w.R + 4))
+    runs = []
+    for b in w.buckets:
+        groups = -(-b.s1 // 512)
+        while groups > 0:
+            runs.append(min(groups, FUSED_MAX_GROUPS))
+            groups -= runs[-1]
+    launches, cnt, blocks = 0, 0, 0
+    for g in runs:
+        if cnt == cap or (cnt > 0 and blocks + g > FUSED_MAX_GROUPS):
+            launches, cnt, blocks = launches + 1, 0, 0
+        cnt, blocks = cnt + 1, blocks + g
+    return launches + (1 if cnt else 0)
+
+
+def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=False):
+    """Builds workload `idx`, runs warmup + steps of the whole step and returns its figures."""
+    cfg = hzp_inputs.config(idx)
+    total_layers = len(cfg["tensors_per_layer"])
+    n_layers = total_layers if args.layers <= 0 else min(args.layers, total_layers)
     rank = cfg["z3"] + 1 if cfg["z1"] > cfg["z3"] + 1 else 0      # a rank with j = 1, k = 1
-    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations, one_alloc_skew=args.one_allocation)
+    # the 70B-class layer stream does not fit with every layer's full bucket resident: its level-3
+    # gather runs through a rotating pool of 8 layers of received shards and 2 destination buckets
+    pool = 8 if cfg["name"] == "dense70b" and n_layers > 8 and not args.separate_allocations else 0
+    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations, l3_pool=pool)
     w.l1_per_layer = args.gather1_per_layer
     phases = set(args.phases.split(","))
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
 
     step = 0
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step += 1
         run_step(w, hzp, step, stream, phases)
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(args.steps):
+    for k in range(steps):
         step += 1
-        run_step(w, hzp, step, stream, phases, evs[k])
+        run_step(w, hzp, step, stream, phases, evs[k])       # events are recorded on `stream`, where the kernels run
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = wall * 1e3 / steps
     ph = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in evs])     # ms
     fused_ms, g1_ms, g3_ms = (float(x) for x in ph.mean(axis=0))
     R = w.R
@@ -553,12 +580,11 @@ def main():
         ach = algo_bytes / launches / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
         return {"kernel": kernel, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": read_traffic(key),
-                "launches_per_step": launches, "avg_launch_us": round(per_launch_ms * 1e3, 2),
+                "traffic_key": key, "launches_per_step": launches, "avg_launch_us": round(per_launch_ms * 1e3, 2),
                 "algorithmic_bytes_per_launch": algo_bytes / launches,
                 "share_of_step_time": round(ms / max(fused_ms + g1_ms + g3_ms, 1e-9), 3)}
 
-    segs_per_launch = min(34, 408 // (R + 4))        # capacity of the kernel-argument segment table
-    fused_launches = -(-w.n_layers // segs_per_launch)
+    fused_launches = fused_launch_count(w)
     rooflines = {}
     if "fused" in phases:
         rooflines["fused_adamw"] = roof("fused_adamw_kernel<R=%d,bf16>" % R, fused_bytes, fused_ms,
@@ -574,31 +600,96 @@ def main():
     if "gather3" in phases:
         rooflines["gather_level3"] = roof("concat_kernel (Z3=%d x S3 -> P)" % w.z3, g3_bytes, g3_ms,
                                           w.n_layers, "concat_l3_%s" % cfg["name"])
+    out = {
+        "cfg": cfg, "w": w if keep else None, "stream": stream if keep else None, "rank": rank, "phases": phases,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "rooflines": rooflines,
+        "fused_ms": fused_ms, "g1_ms": g1_ms, "g3_ms": g3_ms, "fused_bytes": fused_bytes,
+        "fused_launches": fused_launches, "s1_total": w.s1_total, "p_total": w.p_total,
+        "payload_params": w.payload_params, "n_layers": w.n_layers, "R": R, "z3": w.z3, "K": w.K,
+        "l1_per_layer": w.l1_per_layer, "l3_pool": pool,
+    }
+    return out
+
+
+def workload_text(t):
+    cfg = t["cfg"]
+    return ("%s: %d layer buckets, R=%d, Z3=%d, Z1=%d, A=%d, rank %d; step = fused reduce+AdamW on the S1 shards "
+            "(%d launches) + level-1 gather (%s) + level-3 gather per layer%s; `value` is shard parameters per second of "
+            "the whole step, `fused_update` the metric's own kernel"
+            % (cfg["name"], t["n_layers"], t["R"], t["z3"], cfg["z1"], cfg["align"], t["rank"], t["fused_launches"],
+               "one call per layer" if t["l1_per_layer"] else "all layers in one call",
+               " through a rotating pool of %d layers of received shards and 2 buckets" % t["l3_pool"] if t["l3_pool"] else ""))
+
+
+def triple(t):
+    """The {fused, gather1, gather3} rooflines of a timed workload, for the per-workload map."""
+    r = t["rooflines"]
+    short = lambda x: None if x is None else {k: x[k] for k in ("kernel", "achieved", "frac", "avg_launch_us",
+                                                               "launches_per_step", "algorithmic_bytes_per_launch",
+                                                               "traffic", "traffic_key")}
+    return {"workload": workload_text(t), "steps": t["steps"], "ms_per_step": round(t["ms_per_step"], 4),
+            "shard_params_per_step": t["s1_total"],
+            "fused_update_params_per_s": t["s1_total"] / (t["fused_ms"] * 1e-3) if t["fused_ms"] > 0 else None,
+            "fused": short(r.get("fused_adamw")), "gather1": short(r.get("gather_level1")),
+            "gather3": short(r.get("gather_level3"))}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build covers the one-GPU share of the path only; replicas are buffers in one "
+              "GPU's HBM and no collective is issued, so --gpus must be 1 (got %d)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import gc
+
+    import numpy as np
+    import torch
+
+    import hzp_inputs
+    import paper_2510_20111_amd as hzp
+
+    torch.cuda.set_device(0)
+    HEADLINE = 3            # the MoE layer set: the largest workload that fits one GPU
+    head_idx = HEADLINE if args.config < 0 else args.config
+    t = time_workload(head_idx, args, torch, np, hzp, hzp_inputs, args.steps, args.warmup, keep=True)
+    w, stream, cfg, rooflines = t["w"], t["stream"], t["cfg"], t["rooflines"]
+    R, fused_ms = t["R"], t["fused_ms"]
     dominant = max(rooflines.values(), key=lambda r: r["share_of_step_time"])
+    fused_pps = w.s1_total / (fused_ms * 1e-3) if fused_ms > 0 else None
 
     result = {
         "metric": "fused reduce+AdamW shard update: params/sec and achieved HBM GB/s (% of peak)",
-        "value": w.s1_total / (ms_per_step * 1e-3),
+        "value": w.s1_total / (t["ms_per_step"] * 1e-3),
         "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": round(t["ms_per_step"], 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d layer buckets, R=%d, Z3=%d, Z1=%d, A=%d, rank %d; step = fused "
-                               "reduce+AdamW on the S1 shards + level-1 gather (%s) + level-3 gather per layer"
-                               % (cfg["name"], w.n_layers, R, w.z3, cfg["z1"], cfg["align"], rank,
-                                  "one call per layer" if w.l1_per_layer else "all layers in one call"),
+        "config": {"workload": workload_text(t),
                    "shard_params_per_step": w.s1_total, "padded_params": w.p_total,
                    "payload_params": w.payload_params, "padding_params": w.p_total - w.payload_params,
-                   "phases": sorted(phases)},
+                   "phases": sorted(t["phases"])},
+        "fused_update_params_per_s": fused_pps,
+        "fused_update_GBps": rooflines.get("fused_adamw", {}).get("achieved"),
         "roofline": dominant,
         "rooflines": rooflines,
-        "fused_update": {"params_per_s": w.s1_total / (fused_ms * 1e-3) if fused_ms > 0 else None,
+        "fused_update": {"params_per_s": fused_pps,
                          "GBps": rooflines.get("fused_adamw", {}).get("achieved"),
                          "bytes_per_param": 26 + 2 * R, "ms": round(fused_ms, 4)},
-        "phase_ms": {"fused": round(fused_ms, 4), "gather_level1": round(g1_ms, 4),
-                     "gather_level3": round(g3_ms, 4)},
+        "phase_ms": {"fused": round(fused_ms, 4), "gather_level1": round(t["g1_ms"], 4),
+                     "gather_level3": round(t["g3_ms"], 4)},
     }
+    fused_bytes, fused_launches = t["fused_bytes"], t["fused_launches"]
+
+    def roof(kernel, algo_bytes, ms, launches, key):
+        per_launch_ms = ms / launches
+        ach = algo_bytes / launches / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        return {"kernel": kernel, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": read_traffic(key),
+                "traffic_key": key, "launches_per_step": launches, "avg_launch_us": round(per_launch_ms * 1e3, 2),
+                "algorithmic_bytes_per_launch": algo_bytes / launches}
+
     secondary = [x for x in args.secondary.split(",") if x]
     if "overlap" in secondary:
         secondary.remove("overlap")
@@ -621,11 +712,23 @@ def main():
                                    % (getattr(w, "free_z1", 0), w.z3)}[phase]
             launches = fused_launches if phase == "prereduced" else w.n_layers
             result["secondary"][phase] = roof(kname, nbytes, ms, launches, "%s_%s" % (phase, cfg["name"]))
-            result["secondary"][phase].pop("share_of_step_time")
-    if not args.no_probe:
-        result["hbm_probe"] = copy_probe(torch, hzp, stream)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, torch, np)
+    # the other workloads, one after the other, each freed before the next is built
+    if args.config < 0 and args.layers <= 0:
+        configs = {cfg["name"]: triple(t)}
+        t["w"] = t["stream"] = None
+        del w, stream
+        for idx in (0, 1, 2, 4):
+            gc.collect()
+            torch.cuda.empty_cache()
+            o = time_workload(idx, args, torch, np, hzp, hzp_inputs, args.other_steps, min(args.warmup, 3))
+            configs[o["cfg"]["name"]] = triple(o)
+        result["configs"] = {k: configs[k] for k in ("tiny", "dense7b", "dense70b", "moe", "irregular")}
+        gc.collect()
+        torch.cuda.empty_cache()
+    if not args.no_probe:
+        result["hbm_probe"] = copy_probe(torch, hzp, torch.cuda.Stream())
     print(json.dumps(result))
 
 

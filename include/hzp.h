@@ -383,9 +383,7 @@ typedef struct {
     uint32_t cls;               /* class of the buckets this scheduler gathers and reduces */
     uint32_t gather_slots;      /* most regions between prefetch and release at once, >= 1 */
     uint32_t queue_capacity;    /* commands that may wait for the background thread, >= 1 */
-    uint32_t copy_engine;       /* 0: bucket gathers are copy kernels; 1: they are device-to-device copies
-                                 * (hipMemcpyAsync per shard) on the gather stream, which the copy engines
-                                 * carry out without occupying compute units */
+    uint32_t reserved_;         /* 0 */
     uint64_t pool_bytes;        /* 0: the ring is gather_slots equal slots of the largest bucket, so any
                                  * gather_slots regions fit.  Otherwise the ring's size (a multiple of 256):
                                  * a region then takes its own size rounded up to 256 bytes, and a prefetch

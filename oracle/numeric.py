@@ -12,7 +12,8 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SO = os.path.join(_HERE, "libhzp_oracle.so")
+# HZP_ORACLE_LIBRARY names another build of numeric.c (the sanitizer build of the tests); it is loaded as it is
+_SO = os.environ.get("HZP_ORACLE_LIBRARY") or os.path.join(_HERE, "libhzp_oracle.so")
 _SRC = os.path.join(_HERE, "numeric.c")
 _lib = None
 
@@ -36,7 +37,8 @@ class _Hyper(ctypes.Structure):
 def lib():
     global _lib
     if _lib is None:
-        build(force=False)
+        if not os.environ.get("HZP_ORACLE_LIBRARY"):
+            build(force=False)
         L = ctypes.CDLL(_SO)
         L.hzp_oracle_threads.restype = ctypes.c_int
         L.hzp_oracle_bf16_to_f32.restype = ctypes.c_float

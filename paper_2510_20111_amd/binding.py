@@ -9,7 +9,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhzp.so")
+# HZP_LIBRARY names another build of the same library (the host-only sanitizer build of the tests)
+LIB_PATH = os.environ.get("HZP_LIBRARY") or os.path.join(_HERE, "libhzp.so")
 
 HZP_OK, HZP_ERR_INVALID_ARG, HZP_ERR_RANGE, HZP_ERR_UNSUPPORTED, HZP_ERR_ALIGN, HZP_ERR_NOMEM, \
     HZP_ERR_HIP = range(7)
@@ -68,7 +69,7 @@ class TensorInfo(ctypes.Structure):
 
 class SchedDesc(ctypes.Structure):
     _fields_ = [("cls", ctypes.c_uint32), ("gather_slots", ctypes.c_uint32),
-                ("queue_capacity", ctypes.c_uint32), ("copy_engine", ctypes.c_uint32),
+                ("queue_capacity", ctypes.c_uint32), ("reserved_", ctypes.c_uint32),
                 ("pool_bytes", ctypes.c_uint64)]
 
 
@@ -354,9 +355,9 @@ def hzp_gather_tensor(plan, tensor_id, shard_ptrs, tensor_out, stream=None, n_sh
 class Sched:
     """Owner of an ``hzp_sched_t*`` (hzp_sched_create ... hzp_sched_destroy)."""
 
-    def __init__(self, plan, cls=HZP_CLASS_BF16, gather_slots=2, queue_capacity=64, pool_bytes=0, copy_engine=False):
+    def __init__(self, plan, cls=HZP_CLASS_BF16, gather_slots=2, queue_capacity=64, pool_bytes=0):
         self.plan = plan                      # keeps the plan alive
-        desc = SchedDesc(cls, gather_slots, queue_capacity, int(bool(copy_engine)), pool_bytes)
+        desc = SchedDesc(cls, gather_slots, queue_capacity, 0, pool_bytes)
         self.handle = ctypes.c_void_p()
         _check(_L.hzp_sched_create(plan.handle, ctypes.byref(desc), ctypes.byref(self.handle)))
 

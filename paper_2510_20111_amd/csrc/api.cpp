@@ -173,6 +173,11 @@ extern "C" hzp_status_t hzp_gather_layer_static(const hzp_plan_t *plan, uint32_t
         if (reinterpret_cast<uintptr_t>(tensor_out[t]) % es)
             return fail(HZP_ERR_ALIGN, "hzp_gather_layer_static: tensor_out[%u] is not element-aligned", t);
     }
+    if (b->pieces.size() > HZP_STATIC_MAX_PIECES)
+        return fail(HZP_ERR_UNSUPPORTED,
+                    "hzp_gather_layer_static: the bucket has %zu tensor pieces, the fixed table holds %u; "
+                    "use hzp_gather_layer",
+                    b->pieces.size(), (unsigned)HZP_STATIC_MAX_PIECES);
     return launch_unpack_static(*b, shard_ptrs, n_shards, tensor_out, stream);
 }
 

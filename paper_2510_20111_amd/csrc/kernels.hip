@@ -954,11 +954,8 @@ static hzp_status_t fill_table(void *dst, const void *src, size_t bytes, hipStre
 hzp_status_t launch_unpack_static(const BucketRec &b, const void *const *shards, uint32_t n_shards,
                                   void *const *tensors, hipStream_t stream)
 {
-    if (b.pieces.size() > HZP_STATIC_MAX_PIECES)
-        return fail(HZP_ERR_UNSUPPORTED,
-                    "hzp_gather_layer_static: the bucket has %zu tensor pieces, the fixed table holds %u; "
-                    "use hzp_gather_layer",
-                    b.pieces.size(), (unsigned)HZP_STATIC_MAX_PIECES);
+    if (b.pieces.size() > HZP_STATIC_MAX_PIECES)        // refused by the entry point; the table below has this many rows
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layer_static: more tensor pieces than the fixed table holds");
     StaticTables *tab = nullptr;
     hzp_status_t st = scratch_address(&tab);
     if (st != HZP_OK) return st;

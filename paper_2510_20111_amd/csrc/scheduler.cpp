@@ -77,7 +77,6 @@ struct Cmd {
 struct hzp_sched {
     const hzp_plan_t *plan = nullptr;
     uint32_t cls = 0, max_live = 0, queue_capacity = 0;
-    bool copy_engine = false;                   // bucket gathers as device-to-device copies, not kernels
     int device = 0;
     uint64_t pool_bytes = 0;
     uint64_t uniform_bytes = 0;                 // non-zero: every region takes this much (equal slots)
@@ -189,14 +188,6 @@ void worker_main(hzp_sched *s)
                 char *dst = s->pool + cmd.off;
                 if (cmd.is_tensor) {
                     st = hzp_gather_tensor(s->plan, cmd.id, cmd.ptrs.data(), (uint32_t)cmd.ptrs.size(), dst,
-                                           s->gather_stream);
-                } else if (s->copy_engine) {
-                    // One device-to-device copy per shard: the copy engines move the data, no
-                    // workgroup is launched, so a compute kernel that fills the CUs is not disturbed.
-                    const BucketRec *b = find_bucket(s->plan, cmd.id, s->cls);
-                    const size_t bytes = (size_t)b->S3 * (s->cls == HZP_CLASS_F32 ? 4 : 2);
-                    for (size_t j = 0; j < cmd.ptrs.size() && e == hipSuccess; ++j)
-                        e = hipMemcpyAsync(dst + j * bytes, cmd.ptrs[j], bytes, hipMemcpyDeviceToDevice,
                                            s->gather_stream);
                 } else {
                     st = hzp_gather_layer(s->plan, cmd.id, s->cls, 3, cmd.ptrs.data(), (uint32_t)cmd.ptrs.size(),
@@ -408,7 +399,6 @@ extern "C" hzp_status_t hzp_sched_create(const hzp_plan_t *plan, const hzp_sched
         return fail(HZP_ERR_INVALID_ARG, "hzp_sched_create: needs at least one pool slot and one queue entry");
     if (d->pool_bytes % 256 != 0)
         return fail(HZP_ERR_INVALID_ARG, "hzp_sched_create: pool_bytes must be a multiple of 256");
-    if (d->copy_engine > 1) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_create: copy_engine is 0 or 1");
     uint64_t max_p = 0;
     for (const BucketRec &b : plan->buckets)
         if (b.cls == d->cls) max_p = std::max(max_p, b.P);
@@ -420,7 +410,6 @@ extern "C" hzp_status_t hzp_sched_create(const hzp_plan_t *plan, const hzp_sched
     s->cls = d->cls;
     s->max_live = d->gather_slots;
     s->queue_capacity = d->queue_capacity;
-    s->copy_engine = d->copy_engine != 0;
     // Without an explicit size the ring is cut into equal slots of the largest bucket, so that any
     // `gather_slots` regions fit whatever their sizes; with one, a region takes its own size.
     s->pool_bytes = d->pool_bytes ? d->pool_bytes : slot_bytes * d->gather_slots;

@@ -184,6 +184,25 @@ def test_gather_tensor_argument_errors():
     assert _status(f, p, 0, [FAKE] * 2, FAKE + 1, stream=0) == hzp.HZP_ERR_ALIGN          # bf16 needs 2-byte alignment
 
 
+def test_gather_layer_static_argument_errors():
+    p = _plan()
+    f = hzp.hzp_gather_layer_static
+    assert _status(f, p, 0, 0, [FAKE], [FAKE], stream=0) == hzp.HZP_ERR_INVALID_ARG               # needs Z3 = 2 shards
+    assert _status(f, p, 0, 0, [FAKE] * 2, None, stream=0) == hzp.HZP_ERR_INVALID_ARG            # tensor_out is required
+    assert _status(f, p, 0, 0, [FAKE, 0], [FAKE], stream=0) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(f, p, 0, 0, [FAKE, FAKE + 8], [FAKE], stream=0) == hzp.HZP_ERR_ALIGN
+    assert _status(f, p, 0, 0, [FAKE] * 2, [FAKE + 1], stream=0) == hzp.HZP_ERR_ALIGN            # bf16: 2-byte aligned
+    assert _status(f, p, 0, 1, [FAKE] * 2, [FAKE + 2], stream=0) == hzp.HZP_ERR_ALIGN            # fp32: 4-byte aligned
+    assert _status(f, p, 0, 0, [FAKE] * 2, [0], stream=0) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(f, p, 2, 0, [FAKE] * 2, [FAKE], stream=0) == hzp.HZP_ERR_RANGE
+    assert _status(f, p, 1, 1, [FAKE] * 2, [FAKE], stream=0) == hzp.HZP_ERR_RANGE                # no fp32 bucket in layer 1
+    many = hzp.hzp_plan([4097], [8] * 4097, align=8, z3=1, z1=1)     # one piece per tensor: 4097 > 4096
+    assert _status(f, many, 0, 0, [FAKE], [FAKE] * 4097, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+    assert "4096" in hzp.hzp_last_error()
+    big = hzp.hzp_plan([1], [8 * 128], align=8, z3=128, z1=128)
+    assert _status(f, big, 0, 0, [FAKE] * 128, [FAKE], stream=0) == hzp.HZP_ERR_UNSUPPORTED
+
+
 def test_gather_shard_argument_errors():
     p = hzp.hzp_plan([1], [100], align=8, z3=4, z1=6, z2=2)          # S1 = 32, S3 = 48: two owners per shard
     f = hzp.hzp_gather_shard
@@ -266,7 +285,8 @@ int main(void) {
     exe = tmp_path / "plan"
     libdir = os.path.dirname(hzp.LIB_PATH)
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
-                    "-L", libdir, "-l:libhzp.so", "-Wl,-rpath," + libdir, "-Wl,--allow-shlib-undefined"], check=True)
+                    "-L", libdir, "-l:" + os.path.basename(hzp.LIB_PATH), "-Wl,-rpath," + libdir,
+                    "-Wl,--allow-shlib-undefined"], check=True)
     import torch
     env = dict(os.environ)
     env["LD_LIBRARY_PATH"] = os.pathsep.join([os.path.join(os.path.dirname(torch.__file__), "lib"), "/opt/rocm/lib",

@@ -356,36 +356,6 @@ def test_prefetch_ahead_fills_the_pool_and_the_turn_from_forward_to_backward():
     sched.destroy()
 
 
-def test_bucket_gathers_through_the_copy_engines():
-    """copy_engine = 1: the same pipeline with device-to-device copies in place of the copy kernel."""
-    say("scheduler: copy-engine gathers")
-    n_layers = 7
-    oplan, plan, shards = _layers(n_layers, 55)
-    dshards = [[to_dev(s) for s in layer] for layer in shards]
-    sched = hzp.Sched(plan, gather_slots=2, queue_capacity=4, copy_engine=True)
-    consumer = torch.cuda.Stream()
-    busy = torch.randn(2048, 2048, device=DEV)
-    outs = [torch.zeros(oplan["buckets"][l]["P"], dtype=torch.int16, device=DEV) for l in range(n_layers)]
-    torch.cuda.synchronize()
-    sched.prefetch(0, dshards[0], consumer)
-    sched.prefetch(1, dshards[1], consumer)
-    for l in range(n_layers):
-        with torch.cuda.stream(consumer):
-            busy = busy @ busy * 1e-3
-        ptr = sched.acquire(l, consumer)
-        with torch.cuda.stream(consumer):
-            outs[l].copy_(view16(ptr, outs[l].numel()))
-        sched.release(l, consumer)
-        if l + 2 < n_layers:
-            sched.prefetch(l + 2, dshards[l + 2], consumer)
-    consumer.synchronize()
-    sched.drain()
-    for l in range(n_layers):
-        assert np.array_equal(to_host(outs[l], np.uint16), on.gather_concat(shards[l])), l
-    assert sched.stats().gathers_issued == n_layers
-    sched.destroy()
-
-
 def test_prefetch_one_parameter_at_a_time():
     """The paper's granularity: every tensor of a plan prefetched, acquired and released on its own,
     three ahead, through a ring much smaller than a layer."""
