@@ -11,8 +11,9 @@ and resident in HBM before the timed region starts.  Prints ONE JSON line.
 
 The headline workload is the largest of the five that fits one GPU: the full MoE layer set (24
 layers, R = 16, about 200 GB resident).  After it, the same step is timed on the other four
-workloads (fewer repetitions) and reported under "configs": one {fused, gather1, gather3} roofline
-triple per workload.  `--config N` times one workload only.
+workloads (fewer repetitions, each in a child process `bench.py --config N`) and reported under
+"configs": one {fused, gather1, gather3} roofline triple per workload.  `--config N` times one
+workload only.
 """
 import argparse
 import json
@@ -679,6 +680,7 @@ def main():
                          "bytes_per_param": 26 + 2 * R, "ms": round(fused_ms, 4)},
         "phase_ms": {"fused": round(fused_ms, 4), "gather_level1": round(t["g1_ms"], 4),
                      "gather_level3": round(t["g3_ms"], 4)},
+        "workload_name": cfg["name"], "triple": triple(t),
     }
     fused_bytes, fused_launches = t["fused_bytes"], t["fused_launches"]
 
@@ -714,19 +716,30 @@ def main():
             result["secondary"][phase] = roof(kname, nbytes, ms, launches, "%s_%s" % (phase, cfg["name"]))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, torch, np)
-    # the other workloads, one after the other, each freed before the next is built
+    # The other workloads, each in a child process of its own (`bench.py --config N`): where a process's
+    # buffers lie moves the many-stream kernels by a few per cent, and a workload built after the 200 GB
+    # of the headline one were freed lies worse than in a fresh process.
     if args.config < 0 and args.layers <= 0:
+        import subprocess
         configs = {cfg["name"]: triple(t)}
         t["w"] = t["stream"] = None
         del w, stream
-        for idx in (0, 1, 2, 4):
-            gc.collect()
-            torch.cuda.empty_cache()
-            o = time_workload(idx, args, torch, np, hzp, hzp_inputs, args.other_steps, min(args.warmup, 3))
-            configs[o["cfg"]["name"]] = triple(o)
-        result["configs"] = {k: configs[k] for k in ("tiny", "dense7b", "dense70b", "moe", "irregular")}
         gc.collect()
         torch.cuda.empty_cache()
+        for idx in (0, 1, 2, 4):
+            cmd = [sys.executable, os.path.abspath(__file__), "--config", str(idx), "--steps", str(args.other_steps),
+                   "--warmup", str(min(args.warmup, 3)), "--no-cpu-baseline", "--no-probe", "--phases", args.phases]
+            if args.gather1_per_layer:
+                cmd.append("--gather1-per-layer")
+            if args.separate_allocations:
+                cmd.append("--separate-allocations")
+            res = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+            if res.returncode != 0:
+                print(res.stderr[-2000:], file=sys.stderr)
+                raise RuntimeError("bench.py --config %d failed" % idx)
+            child = json.loads([l for l in res.stdout.splitlines() if l.startswith("{")][-1])
+            configs[child["workload_name"]] = child["triple"]
+        result["configs"] = {k: configs[k] for k in ("tiny", "dense7b", "dense70b", "moe", "irregular")}
     if not args.no_probe:
         result["hbm_probe"] = copy_probe(torch, hzp, torch.cuda.Stream())
     print(json.dumps(result))
