@@ -240,3 +240,45 @@ def choose_groups(N, dp, node, budget_bytes):
             if hzp_memory_bytes(N, z1, z3, z3) <= budget_bytes and (best is None or (z3, z1) < best):
                 best = (z3, z1)
     return None if best is None else (best[1], best[0], best[0])
+
+
+# ---------------------------------------------------------------------------------------------
+# One arena for a rank's persistent buffers of one class.
+#
+# Section 4.2 keeps communication buffers in pre-allocated, contiguous memory; the paper gives no
+# layout.  The reading used here: a rank's buffers of one class are streams (R gradient
+# contributions, master, momentum, variance, cast parameters, the received ZeRO-1 pieces of the
+# other owners, the rank's ZeRO-3 shard, the received ZeRO-3 shards), each stream holds the slices
+# of all buckets of the class back to back in bucket order, and the streams follow one another
+# inside one allocation, each starting on a multiple of ARENA_ALIGN bytes.
+# ---------------------------------------------------------------------------------------------
+ARENA_ALIGN = 2 << 20
+STREAM_GRAD, STREAM_MASTER, STREAM_M, STREAM_V, STREAM_PARAM_OUT, STREAM_RECV1, STREAM_SHARD3, STREAM_RECV3 = range(8)
+
+
+def arena_streams(plan, cls, R, grad_bytes):
+    """[(kind, index, level, element_bytes)] in arena order.  level 1: ZeRO-1 slices, 3: ZeRO-3."""
+    eb = _ELEM_BYTES[cls]
+    out = [(STREAM_GRAD, r, 1, grad_bytes) for r in range(R)]
+    out += [(STREAM_MASTER, 0, 1, 4), (STREAM_M, 0, 1, 4), (STREAM_V, 0, 1, 4), (STREAM_PARAM_OUT, 0, 1, eb)]
+    if plan["K"]:                                      # the K-1 other owners of the rank's ZeRO-3 shard
+        out += [(STREAM_RECV1, k, 1, eb) for k in range(plan["K"] - 1)]
+    out += [(STREAM_SHARD3, 0, 3, eb)]
+    out += [(STREAM_RECV3, j, 3, eb) for j in range(plan["z3"] - 1)]
+    return out
+
+
+def arena_layout(plan, cls, R, grad_bytes):
+    """(total_bytes, {(kind, index, layer): (byte_offset, bytes)}) for the class's buckets."""
+    buckets = [b for b in plan["buckets"] if b["cls"] == cls]
+    if not buckets:
+        raise PlanError("the plan has no bucket of that class")
+    slices = {}
+    pos = 0
+    for kind, index, level, eb in arena_streams(plan, cls, R, grad_bytes):
+        pos = round_up(pos, ARENA_ALIGN)
+        for b in buckets:
+            n = b["S1"] if level == 1 else b["S3"]
+            slices[kind, index, b["layer"]] = (pos, n * eb)
+            pos += n * eb
+    return pos, slices

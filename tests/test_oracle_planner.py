@@ -329,3 +329,42 @@ def test_workload_shapes():
     plan = op.make_plan(c4["tensors_per_layer"], c4["tensor_numel"], c4["align"], c4["z3"],
                         c4["z1"], tensor_class=c4["tensor_class"])
     assert len(plan["buckets"]) == 128                       # a bf16 and an fp32 bucket per group
+
+
+# ------------------------------------------------------------------ one arena per rank and class
+
+def test_arena_layout_invariants_and_hand_values():
+    """Streams follow one another on 2 MiB boundaries, slices of a stream lie back to back in bucket
+    order, nothing overlaps, every slice has the length of the shard it holds."""
+    plan = op.make_plan([2, 1, 2], [1000, 77, 4096, 300000, 9], 16, 4, 8, tensor_class=[0, 1, 0, 0, 1])
+    for cls, R, gb in ((0, 3, 2), (0, 2, 4), (1, 5, 4)):
+        total, sl = op.arena_layout(plan, cls, R, gb)
+        buckets = [b for b in plan["buckets"] if b["cls"] == cls]
+        streams = op.arena_streams(plan, cls, R, gb)
+        assert len(streams) == R + 4 + (plan["K"] - 1) + 1 + (plan["z3"] - 1)
+        assert len(sl) == len(streams) * len(buckets)
+        spans = sorted((off, off + n) for off, n in sl.values())
+        assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))            # pairwise disjoint
+        assert spans[-1][1] == total
+        for kind, index, level, eb in streams:
+            first = sl[kind, index, buckets[0]["layer"]][0]
+            assert first % op.ARENA_ALIGN == 0
+            pos = first
+            for b in buckets:
+                off, n = sl[kind, index, b["layer"]]
+                assert off == pos and n == eb * (b["S1"] if level == 1 else b["S3"])
+                assert off % 16 == 0                                            # shards are multiples of A >= 8 elements
+                pos += n
+    # hand values: one bf16 bucket of P = 2^20 elements, Z3 = 2, Z1 = 4, R = 2 bf16 contributions:
+    # S1 = 262144 (512 KiB in bf16, 1 MiB in fp32), S3 = 524288 (1 MiB); every stream fits 2 MiB
+    plan = op.make_plan([1], [1 << 20], 8, 2, 4)
+    total, sl = op.arena_layout(plan, 0, 2, 2)
+    M = 2 << 20
+    assert sl[op.STREAM_GRAD, 0, 0] == (0, 524288) and sl[op.STREAM_GRAD, 1, 0] == (M, 524288)
+    assert sl[op.STREAM_MASTER, 0, 0] == (2 * M, 1048576) and sl[op.STREAM_V, 0, 0] == (4 * M, 1048576)
+    assert sl[op.STREAM_PARAM_OUT, 0, 0] == (5 * M, 524288)
+    assert sl[op.STREAM_RECV1, 0, 0] == (6 * M, 524288)                         # K - 1 = 1 other owner
+    assert sl[op.STREAM_SHARD3, 0, 0] == (7 * M, 1048576)
+    assert sl[op.STREAM_RECV3, 0, 0] == (8 * M, 1048576) and total == 8 * M + 1048576
+    with pytest.raises(op.PlanError):
+        op.arena_layout(plan, 1, 2, 4)                                          # no fp32 bucket
