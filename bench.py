@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--separate-allocations", action="store_true",
                     help="give every slice its own allocation instead of per-kind arenas (layout experiment)")
+    ap.add_argument("--layout", default="arena", choices=["arena", "kinds"],
+                    help="arena: the rank's streams in one allocation at the planner's offsets (default); kinds: one "
+                         "allocation per stream kind")
     ap.add_argument("--gather1-per-layer", action="store_true",
                     help="issue the level-1 gather as one call per layer instead of one call for all layers")
     ap.add_argument("--phases", default="fused,gather1,gather3",
@@ -54,13 +57,16 @@ def parse_args():
 class Workload:
     """Device buffers and pre-marshalled pointer arrays of one rank's share.
 
-    Layout: one arena per stream kind (replica r's gradient slices, master, momentum, variance,
-    bf16 output, received ZeRO-1 pieces, ZeRO-3 shards, received shards, layer buckets), each
-    holding the slices of all layer buckets back to back in bucket order -- the offset of a
-    bucket's slice is the plan's `base` divided by the group size.  `separate=True` gives every
-    slice its own allocation instead (a layout experiment: it streams about 4 % slower)."""
+    Layout "arena" (default): the rank's persistent streams (replica r's gradient slices, master,
+    momentum, variance, bf16 output, received ZeRO-1 pieces, the ZeRO-3 shard, received shards) lie
+    in ONE allocation at the offsets the planner gives (hzp_plan_arena / hzp_plan_arena_slice: every
+    stream on a 2 MiB boundary, the slices of all layer buckets back to back); only the gathered
+    layer buckets (and a rotating pool's shards) are allocations of their own.  Layout "kinds": one
+    allocation per stream kind, same order inside (the earlier default: 1-4 % slower on average and
+    much less repeatable from process to process).  `separate=True` gives every slice its own
+    allocation (slower again)."""
 
-    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False, l3_pool=0):
+    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False, l3_pool=0, layout="arena"):
         """l3_pool > 0: the level-3 gather streams through a rotating pool (the cyclic buffers of
         Section 4.2): the received ZeRO-3 shards of only `l3_pool` layers and two destination buckets
         are resident, layer l using slot l % l3_pool and bucket l % 2.  For layer streams whose full
@@ -81,15 +87,46 @@ class Workload:
         j, k, i = self.plan.rank(rank)
         bf16, f32 = torch.bfloat16, torch.float32
         arenas = {}
+        self.layout = "separate" if separate else layout
+        big, big_off = None, 0
+        if self.layout == "arena":
+            A = hzp.HZP_ARENA_ALIGN
+            whole = torch.empty(self.plan.arena(0, self.R) + A, dtype=torch.uint8, device=dev)
+            big_off = (-whole.data_ptr()) % A          # the arena starts on a multiple of HZP_ARENA_ALIGN
+            big = self.arena_buffer = whole
+
+        def stream_of(name):
+            """(hzp stream, index) of an arena name, or None for buffers outside the planner's arena."""
+            if name[0] == "g" and name[1:].isdigit():
+                return hzp.HZP_STREAM_GRAD, int(name[1:])
+            if name in ("p", "m", "v", "o", "s3"):
+                return {"p": hzp.HZP_STREAM_MASTER, "m": hzp.HZP_STREAM_M, "v": hzp.HZP_STREAM_V,
+                        "o": hzp.HZP_STREAM_PARAM_OUT, "s3": hzp.HZP_STREAM_SHARD3}[name], 0
+            if name.startswith("recv1_"):
+                kk = int(name[6:])
+                return hzp.HZP_STREAM_RECV1, kk if kk < k else kk - 1      # the K-1 owners other than this rank
+            if name.startswith("recv3_") and not l3_pool:
+                jj = int(name[6:])
+                return hzp.HZP_STREAM_RECV3, jj if jj < j else jj - 1
+            return None
 
         def arena(name, total, dtype):
             if name not in arenas:
                 arenas[name] = torch.empty(total, dtype=dtype, device=dev)
             return arenas[name]
 
-        def piece(name, total, dtype, begin, n, fill=None):
+        def piece(name, total, dtype, begin, n, fill=None, layer=None):
             """Slice [begin, begin+n) of the arena `name`, or an allocation of its own."""
-            t = torch.empty(n, dtype=dtype, device=dev) if separate else arena(name, total, dtype)[begin:begin + n]
+            st = stream_of(name) if (big is not None and layer is not None) else None
+            if separate:
+                t = torch.empty(n, dtype=dtype, device=dev)
+            elif st is not None:
+                off, nbytes = self.plan.arena_slice(0, self.R, st[0], st[1], layer)
+                t = big[big_off + off:big_off + off + nbytes].view(dtype)
+                assert t.numel() == n
+                arenas.setdefault(name, t)
+            else:
+                t = arena(name, total, dtype)[begin:begin + n]
             if fill is not None:
                 t.copy_(fill)
             return t
@@ -111,17 +148,17 @@ class Workload:
             o1, o3 = b.base // cfg["z1"], b.base // cfg["z3"]       # arena offsets of this bucket's slices
             pad = None if b.payload_end == b.padded else ranges
             grads = [piece("g%d" % r, self.s1_total, bf16, o1, n,
-                           hzp_inputs.device_normal(n, cfg["sigma"], 1000003 * l + 17 * r + 1, dev, bf16, pad, beg))
+                           hzp_inputs.device_normal(n, cfg["sigma"], 1000003 * l + 17 * r + 1, dev, bf16, pad, beg), layer=l)
                      for r in range(self.R)]
             p = piece("p", self.s1_total, f32, o1, n,
-                      hzp_inputs.device_normal(n, 0.02, 1000003 * l + 7919, dev, f32, pad, beg))
-            m = piece("m", self.s1_total, f32, o1, n).zero_()
-            v = piece("v", self.s1_total, f32, o1, n).zero_()
-            out = piece("o", self.s1_total, bf16, o1, n).zero_()
+                      hzp_inputs.device_normal(n, 0.02, 1000003 * l + 7919, dev, f32, pad, beg), layer=l)
+            m = piece("m", self.s1_total, f32, o1, n, layer=l).zero_()
+            v = piece("v", self.s1_total, f32, o1, n, layer=l).zero_()
+            out = piece("o", self.s1_total, bf16, o1, n, layer=l).zero_()
             # level 1: this rank's output is owner k; the other K-1 owners' pieces are "received"
-            owners = [out if kk == k else piece("recv1_%d" % kk, self.s1_total, bf16, o1, n).normal_()
+            owners = [out if kk == k else piece("recv1_%d" % kk, self.s1_total, bf16, o1, n, layer=l).normal_()
                       for kk in range(self.K)]
-            shard3 = piece("s3", self.s3_total, bf16, o3, b.s3).zero_()
+            shard3 = piece("s3", self.s3_total, bf16, o3, b.s3, layer=l).zero_()
             # level 3: this rank's shard is j; the other Z3-1 shards are "received"
             if l3_pool:
                 slot = l % l3_pool
@@ -135,7 +172,7 @@ class Workload:
                             shards[jj].normal_()
                 bucket = piece("bucket", 2 * p_max, bf16, (l % 2) * p_max, b.padded)
             else:
-                shards = [shard3 if jj == j else piece("recv3_%d" % jj, self.s3_total, bf16, o3, b.s3).normal_()
+                shards = [shard3 if jj == j else piece("recv3_%d" % jj, self.s3_total, bf16, o3, b.s3, layer=l).normal_()
                           for jj in range(self.z3)]
                 bucket = piece("bucket", self.p_total, bf16, b.base, b.padded)
             self.keep.append((grads, p, m, v, out, owners, shard3, shards, bucket))
@@ -549,7 +586,8 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
     # the 70B-class layer stream does not fit with every layer's full bucket resident: its level-3
     # gather runs through a rotating pool of 8 layers of received shards and 2 destination buckets
     pool = 8 if cfg["name"] == "dense70b" and n_layers > 8 and not args.separate_allocations else 0
-    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations, l3_pool=pool)
+    w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations, l3_pool=pool,
+                 layout=args.layout)
     w.l1_per_layer = args.gather1_per_layer
     phases = set(args.phases.split(","))
     stream = torch.cuda.Stream()
@@ -607,17 +645,19 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
         "fused_ms": fused_ms, "g1_ms": g1_ms, "g3_ms": g3_ms, "fused_bytes": fused_bytes,
         "fused_launches": fused_launches, "s1_total": w.s1_total, "p_total": w.p_total,
         "payload_params": w.payload_params, "n_layers": w.n_layers, "R": R, "z3": w.z3, "K": w.K,
-        "l1_per_layer": w.l1_per_layer, "l3_pool": pool,
+        "l1_per_layer": w.l1_per_layer, "l3_pool": pool, "layout": w.layout,
     }
     return out
 
 
 def workload_text(t):
     cfg = t["cfg"]
-    return ("%s: %d layer buckets, R=%d, Z3=%d, Z1=%d, A=%d, rank %d; step = fused reduce+AdamW on the S1 shards "
+    where = {"arena": "the rank's streams in one allocation at the planner's offsets (hzp_plan_arena)",
+             "kinds": "one allocation per stream kind", "separate": "one allocation per slice"}[t["layout"]]
+    return ("%s: %d layer buckets, R=%d, Z3=%d, Z1=%d, A=%d, rank %d, %s; step = fused reduce+AdamW on the S1 shards "
             "(%d launches) + level-1 gather (%s) + level-3 gather per layer%s; `value` is shard parameters per second of "
             "the whole step, `fused_update` the metric's own kernel"
-            % (cfg["name"], t["n_layers"], t["R"], t["z3"], cfg["z1"], cfg["align"], t["rank"], t["fused_launches"],
+            % (cfg["name"], t["n_layers"], t["R"], t["z3"], cfg["z1"], cfg["align"], t["rank"], where, t["fused_launches"],
                "one call per layer" if t["l1_per_layer"] else "all layers in one call",
                " through a rotating pool of %d layers of received shards and 2 buckets" % t["l3_pool"] if t["l3_pool"] else ""))
 
@@ -733,6 +773,7 @@ def main():
                 cmd.append("--gather1-per-layer")
             if args.separate_allocations:
                 cmd.append("--separate-allocations")
+            cmd += ["--layout", args.layout]
             res = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
             if res.returncode != 0:
                 print(res.stderr[-2000:], file=sys.stderr)

@@ -183,6 +183,41 @@ hzp_status_t hzp_plan_shard(const hzp_plan_t *plan, uint32_t layer, uint32_t cls
 hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt_bytes, uint64_t *grad_bytes,
                             uint64_t *param_bytes);
 
+/* ------------------------------------------------------------------------------------------
+ * One arena for a rank's persistent buffers of one class.
+ *
+ * Section 4.2 keeps communication buffers in pre-allocated contiguous memory and gives no layout.
+ * This library's: the rank's buffers are streams -- R gradient contributions, master, momentum,
+ * variance, cast parameters, the received ZeRO-1 pieces of the K-1 other owners of its ZeRO-3
+ * shard, that shard, the Z3-1 received ZeRO-3 shards -- in that order inside ONE allocation; every
+ * stream starts on a multiple of HZP_ARENA_ALIGN bytes, an odd number of HZP_ARENA_ALIGN units
+ * after the start of the stream before it, and holds the slices (S1 or S3 elements) of all
+ * buckets of the class back to back in bucket order.  The caller allocates total_bytes once,
+ * aligned to HZP_ARENA_ALIGN, and hands `base + byte_offset` to the entry points; every offset is a
+ * multiple of 16.  Why one allocation: the fused update reads R+3 and writes 4 of these streams at
+ * the same relative position, and how their addresses lie against one another moves its bandwidth
+ * by several per cent; separate allocations land wherever the driver puts them (measured on MI355X
+ * over 5 processes each, 7B-class share: 5.90-6.34 TB/s with one allocation per stream kind,
+ * 6.46-6.52 with this arena; streams exactly 256 MiB apart: 5.96; even numbers of units apart: 1-2 %
+ * below odd ones on average; a 4 KiB stagger between the streams: 6.1-6.2).
+ *   cls, R, grad_dtype : class of the buckets, number of contributions (0 .. HZP_MAX_REPLICAS) and their
+ *                        element type (an hzp_grad_dtype_t) -- they fix the streams and their sizes
+ *   stream, index      : an hzp_stream_t; index r < R for GRAD, k < K-1 for RECV1, j < Z3-1 for RECV3, else 0
+ * Host-only integer work.  Errors: INVALID_ARG (NULL, unknown gradient type), RANGE (class without a
+ * bucket, layer, stream, index), UNSUPPORTED (R too large; RECV1 when z3 does not divide z1).
+ * ------------------------------------------------------------------------------------------ */
+#define HZP_ARENA_ALIGN (2u << 20)
+typedef enum {
+    HZP_STREAM_GRAD = 0, HZP_STREAM_MASTER = 1, HZP_STREAM_M = 2, HZP_STREAM_V = 3, HZP_STREAM_PARAM_OUT = 4,
+    HZP_STREAM_RECV1 = 5, HZP_STREAM_SHARD3 = 6, HZP_STREAM_RECV3 = 7
+} hzp_stream_t;
+hzp_status_t hzp_plan_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
+                            uint64_t *total_bytes);
+/* Where bucket (layer, cls)'s slice of a stream lies in the arena, and its size in bytes. */
+hzp_status_t hzp_plan_arena_slice(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
+                                  uint32_t stream, uint32_t index, uint32_t layer, uint64_t *byte_offset,
+                                  uint64_t *bytes);
+
 /* Static model-state memory per device of Section 4.1.1 for N parameters,
  *     M_hzp = 12N/Z1 + 4N/Z2 + 2N/Z3   bytes,
  * evaluated exactly and rounded up to a whole byte.  Z1 = Z2 = Z3 = Z gives M_zp = 18N/Z, and

@@ -250,7 +250,9 @@ def choose_groups(N, dp, node, budget_bytes):
 # contributions, master, momentum, variance, cast parameters, the received ZeRO-1 pieces of the
 # other owners, the rank's ZeRO-3 shard, the received ZeRO-3 shards), each stream holds the slices
 # of all buckets of the class back to back in bucket order, and the streams follow one another
-# inside one allocation, each starting on a multiple of ARENA_ALIGN bytes.
+# inside one allocation, each starting on a multiple of ARENA_ALIGN bytes, an ODD number of
+# ARENA_ALIGN units after the start of the stream before it (streams that are read at the same
+# relative position should not lie a large power of two apart).
 # ---------------------------------------------------------------------------------------------
 ARENA_ALIGN = 2 << 20
 STREAM_GRAD, STREAM_MASTER, STREAM_M, STREAM_V, STREAM_PARAM_OUT, STREAM_RECV1, STREAM_SHARD3, STREAM_RECV3 = range(8)
@@ -275,8 +277,12 @@ def arena_layout(plan, cls, R, grad_bytes):
         raise PlanError("the plan has no bucket of that class")
     slices = {}
     pos = 0
+    prev_start = None
     for kind, index, level, eb in arena_streams(plan, cls, R, grad_bytes):
         pos = round_up(pos, ARENA_ALIGN)
+        if prev_start is not None and ((pos - prev_start) // ARENA_ALIGN) % 2 == 0:
+            pos += ARENA_ALIGN                      # odd spacing between consecutive streams
+        prev_start = pos
         for b in buckets:
             n = b["S1"] if level == 1 else b["S3"]
             slices[kind, index, b["layer"]] = (pos, n * eb)

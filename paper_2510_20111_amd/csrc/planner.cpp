@@ -315,6 +315,126 @@ extern "C" hzp_status_t hzp_plan_cover(const hzp_plan_t *plan, uint32_t layer, u
     return HZP_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// One arena for a rank's persistent buffers of one class.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+// Where a stream's first slice starts and what a slice of it measures.
+struct ArenaWalk {
+    uint64_t total = 0;             // bytes of the whole arena
+    uint64_t stream_base = 0;       // of the stream asked for
+    uint32_t stream_level = 0;      // 1: ZeRO-1 slices, 3: ZeRO-3 slices
+    uint32_t stream_elem = 0;       // bytes per element
+    bool found = false;
+};
+
+// Lays the streams out one after the other (each on a multiple of HZP_ARENA_ALIGN) and notes the one
+// asked for.  s1_bytes / s3_bytes: the class's ZeRO-1 / ZeRO-3 slices of all buckets, in elements.
+ArenaWalk walk_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_bytes, uint64_t s1_total,
+                     uint64_t s3_total, uint32_t want_stream, uint32_t want_index)
+{
+    const uint32_t eb = cls == HZP_CLASS_F32 ? 4u : 2u;
+    struct Kind {
+        uint32_t stream, count, level, elem;
+    };
+    const Kind kinds[] = {
+        {HZP_STREAM_GRAD, R, 1, grad_bytes},          {HZP_STREAM_MASTER, 1, 1, 4},
+        {HZP_STREAM_M, 1, 1, 4},                      {HZP_STREAM_V, 1, 1, 4},
+        {HZP_STREAM_PARAM_OUT, 1, 1, eb},             {HZP_STREAM_RECV1, plan->K ? plan->K - 1 : 0, 1, eb},
+        {HZP_STREAM_SHARD3, 1, 3, eb},                {HZP_STREAM_RECV3, plan->z3 - 1, 3, eb},
+    };
+    ArenaWalk w;
+    uint64_t end = 0;               // end of the data placed so far
+    uint64_t last_start = 0;
+    bool first = true;
+    for (const Kind &k : kinds)
+        for (uint32_t i = 0; i < k.count; ++i) {
+            uint64_t start = (end + HZP_ARENA_ALIGN - 1) / HZP_ARENA_ALIGN * HZP_ARENA_ALIGN;
+            // consecutive streams lie an odd number of alignment units apart
+            if (!first && ((start - last_start) / HZP_ARENA_ALIGN) % 2 == 0) start += HZP_ARENA_ALIGN;
+            first = false;
+            last_start = start;
+            if (k.stream == want_stream && i == want_index) {
+                w.stream_base = start;
+                w.stream_level = k.level;
+                w.stream_elem = k.elem;
+                w.found = true;
+            }
+            end = start + (k.level == 1 ? s1_total : s3_total) * k.elem;
+        }
+    w.total = end;
+    return w;
+}
+
+hzp_status_t arena_args(const char *who, const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
+                        uint32_t *grad_bytes, uint64_t *s1_total, uint64_t *s3_total)
+{
+    if (!plan) return fail(HZP_ERR_INVALID_ARG, "%s: NULL plan", who);
+    if (cls > 1) return fail(HZP_ERR_RANGE, "%s: class %u", who, cls);
+    if (grad_dtype > HZP_GRAD_F32) return fail(HZP_ERR_INVALID_ARG, "%s: unknown gradient type %u", who, grad_dtype);
+    if (R > HZP_MAX_REPLICAS) return fail(HZP_ERR_UNSUPPORTED, "%s: R=%u exceeds %u", who, R, HZP_MAX_REPLICAS);
+    *grad_bytes = grad_dtype == HZP_GRAD_DEFAULT ? (cls == HZP_CLASS_F32 ? 4u : 2u) : grad_dtype == HZP_GRAD_F32 ? 4u : 2u;
+    uint64_t a = 0, c = 0;
+    bool any = false;
+    for (const BucketRec &b : plan->buckets)
+        if (b.cls == cls) {
+            a += b.S1;
+            c += b.S3;
+            any = true;
+        }
+    if (!any) return fail(HZP_ERR_RANGE, "%s: the plan has no bucket of class %u", who, cls);
+    // at most R + 4 + K + Z3 streams of at most 4 bytes x (a or c) each, plus the alignment gaps
+    const unsigned __int128 bound = ((unsigned __int128)R + 4 + plan->K + plan->z3) *
+                                    (4 * (unsigned __int128)(a > c ? a : c) + HZP_ARENA_ALIGN);
+    if (bound >> 63) return fail(HZP_ERR_UNSUPPORTED, "%s: the arena would exceed 2^63 bytes", who);
+    *s1_total = a;
+    *s3_total = c;
+    return HZP_OK;
+}
+
+}  // namespace
+
+extern "C" hzp_status_t hzp_plan_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
+                                       uint64_t *total_bytes)
+{
+    if (!total_bytes) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_arena: NULL output");
+    uint32_t gb = 0;
+    uint64_t s1 = 0, s3 = 0;
+    hzp_status_t st = arena_args("hzp_plan_arena", plan, cls, R, grad_dtype, &gb, &s1, &s3);
+    if (st != HZP_OK) return st;
+    *total_bytes = walk_arena(plan, cls, R, gb, s1, s3, ~0u, 0).total;
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_plan_arena_slice(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
+                                             uint32_t stream, uint32_t index, uint32_t layer, uint64_t *byte_offset,
+                                             uint64_t *bytes)
+{
+    if (!byte_offset || !bytes) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_arena_slice: NULL output");
+    uint32_t gb = 0;
+    uint64_t s1 = 0, s3 = 0;
+    hzp_status_t st = arena_args("hzp_plan_arena_slice", plan, cls, R, grad_dtype, &gb, &s1, &s3);
+    if (st != HZP_OK) return st;
+    const BucketRec *b = find_bucket(plan, layer, cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_plan_arena_slice: no bucket (layer %u, class %u)", layer, cls);
+    if (stream > HZP_STREAM_RECV3) return fail(HZP_ERR_RANGE, "hzp_plan_arena_slice: unknown stream %u", stream);
+    if (stream == HZP_STREAM_RECV1 && plan->K == 0)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_plan_arena_slice: z3=%u does not divide z1=%u: a ZeRO-3 shard has no "
+                                         "whole ZeRO-1 owners", plan->z3, plan->z1);
+    const ArenaWalk w = walk_arena(plan, cls, R, gb, s1, s3, stream, index);
+    if (!w.found) return fail(HZP_ERR_RANGE, "hzp_plan_arena_slice: stream %u has no index %u", stream, index);
+    // the slices of the class's earlier buckets lie in front of this bucket's
+    uint64_t before = 0;
+    for (const BucketRec &x : plan->buckets) {
+        if (&x == b) break;
+        if (x.cls == cls) before += w.stream_level == 1 ? x.S1 : x.S3;
+    }
+    *byte_offset = w.stream_base + before * w.stream_elem;
+    *bytes = (w.stream_level == 1 ? b->S1 : b->S3) * w.stream_elem;
+    return HZP_OK;
+}
+
 extern "C" hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt, uint64_t *grad, uint64_t *par)
 {
     if (!plan) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_bytes: NULL plan");

@@ -346,6 +346,11 @@ def test_arena_layout_invariants_and_hand_values():
         spans = sorted((off, off + n) for off, n in sl.values())
         assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))            # pairwise disjoint
         assert spans[-1][1] == total
+        starts = [sl[kind, index, buckets[0]["layer"]][0] for kind, index, level, eb in streams]
+        for a, b, (kind, index, level, eb) in zip(starts, starts[1:], streams):
+            size = eb * sum(x["S1"] if level == 1 else x["S3"] for x in buckets)
+            units = (b - a) // op.ARENA_ALIGN
+            assert units % 2 == 1 and a + size <= b < a + size + 2 * op.ARENA_ALIGN   # odd spacing, no more than needed
         for kind, index, level, eb in streams:
             first = sl[kind, index, buckets[0]["layer"]][0]
             assert first % op.ARENA_ALIGN == 0
@@ -368,3 +373,11 @@ def test_arena_layout_invariants_and_hand_values():
     assert sl[op.STREAM_RECV3, 0, 0] == (8 * M, 1048576) and total == 8 * M + 1048576
     with pytest.raises(op.PlanError):
         op.arena_layout(plan, 1, 2, 4)                                          # no fp32 bucket
+    # streams of an even number of 2 MiB units get one more unit of spacing: P = 2^23, Z1 = Z3 = 1, R = 1:
+    # 16 MiB of bf16 (8 units -> spacing 9), 32 MiB of fp32 (16 units -> spacing 17)
+    plan = op.make_plan([1], [1 << 23], 8, 1, 1)
+    total, sl = op.arena_layout(plan, 0, 1, 2)
+    assert sl[op.STREAM_GRAD, 0, 0] == (0, 16 * M // 2) and sl[op.STREAM_MASTER, 0, 0] == (9 * M, 16 * M)
+    assert sl[op.STREAM_M, 0, 0] == (26 * M, 16 * M) and sl[op.STREAM_V, 0, 0] == (43 * M, 16 * M)
+    assert sl[op.STREAM_PARAM_OUT, 0, 0] == (60 * M, 8 * M) and sl[op.STREAM_SHARD3, 0, 0] == (69 * M, 8 * M)
+    assert total == 77 * M

@@ -1,4 +1,5 @@
 """The library's planner against the layout oracle, bit for bit (runs without a GPU)."""
+import pytest
 from hypothesis import given, settings, strategies as st
 
 import hzp_inputs
@@ -150,3 +151,56 @@ def test_choose_groups_matches_the_oracle():
         with pytest.raises(hzp.HzpError) as e:
             hzp.hzp_choose_groups(*bad)
         assert e.value.status == hzp.HZP_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ arena layout
+
+@given(desc=descriptors(), R=st.integers(0, 32), gd=st.sampled_from([0, 1, 2]))
+@settings(max_examples=120, deadline=None)
+def test_arena_layout_matches_the_oracle(desc, R, gd):
+    oplan = op.make_plan(**desc)
+    plan = hzp.hzp_plan(**desc)
+    for cls in (0, 1):
+        buckets = [b for b in oplan["buckets"] if b["cls"] == cls]
+        if not buckets:
+            with pytest.raises(hzp.HzpError) as e:
+                plan.arena(cls, R, gd)
+            assert e.value.status == hzp.HZP_ERR_RANGE
+            continue
+        gb = (4 if cls == 1 else 2) if gd == 0 else (4 if gd == 2 else 2)
+        total, slices = op.arena_layout(oplan, cls, R, gb)
+        assert plan.arena(cls, R, gd) == total
+        for (kind, index, layer), want in slices.items():
+            assert plan.arena_slice(cls, R, kind, index, layer, gd) == want, (kind, index, layer)
+        # indices one past the end of each stream are refused
+        for kind, count in ((hzp.HZP_STREAM_GRAD, R), (hzp.HZP_STREAM_MASTER, 1), (hzp.HZP_STREAM_RECV3, oplan["z3"] - 1)):
+            with pytest.raises(hzp.HzpError) as e:
+                plan.arena_slice(cls, R, kind, count, buckets[0]["layer"], gd)
+            assert e.value.status == hzp.HZP_ERR_RANGE
+        if oplan["K"]:
+            with pytest.raises(hzp.HzpError) as e:
+                plan.arena_slice(cls, R, hzp.HZP_STREAM_RECV1, oplan["K"] - 1, buckets[0]["layer"], gd)
+            assert e.value.status == hzp.HZP_ERR_RANGE
+        else:
+            with pytest.raises(hzp.HzpError) as e:
+                plan.arena_slice(cls, R, hzp.HZP_STREAM_RECV1, 0, buckets[0]["layer"], gd)
+            assert e.value.status == hzp.HZP_ERR_UNSUPPORTED
+
+
+def test_arena_argument_errors():
+    plan = hzp.hzp_plan([2, 1], [100, 40, 9], align=8, z3=2, z1=4, tensor_class=[0, 1, 0])
+    def status(fn, *a):
+        with pytest.raises(hzp.HzpError) as e:
+            fn(*a)
+        return e.value.status
+    assert status(plan.arena, 2, 1) == hzp.HZP_ERR_RANGE
+    assert status(plan.arena, 0, 33) == hzp.HZP_ERR_UNSUPPORTED
+    assert status(plan.arena, 0, 1, 3) == hzp.HZP_ERR_INVALID_ARG
+    assert status(plan.arena_slice, 0, 1, 8, 0, 0) == hzp.HZP_ERR_RANGE          # unknown stream
+    assert status(plan.arena_slice, 1, 1, 0, 0, 1) == hzp.HZP_ERR_RANGE          # layer 1 has no fp32 bucket
+    assert status(plan.arena_slice, 0, 1, 0, 0, 2) == hzp.HZP_ERR_RANGE          # no layer 2
+    huge = hzp.hzp_plan([1] * 60000, [1 << 40] * 60000, align=8, z3=1, z1=1)   # 6.6e16 elements in all
+    assert status(huge.arena, 0, 32) == hzp.HZP_ERR_UNSUPPORTED                # 37 streams of 4 bytes each pass 2^63
+    # 5 streams (master, m, v, cast parameters, ZeRO-3 shard), each an even number of 2 MiB units long: one more
+    # unit between consecutive streams
+    assert huge.arena(0, 0) == 60000 * (1 << 40) * (4 * 3 + 2 + 2) + 4 * hzp.HZP_ARENA_ALIGN
