@@ -250,11 +250,15 @@ def choose_groups(N, dp, node, budget_bytes):
 # contributions, master, momentum, variance, cast parameters, the received ZeRO-1 pieces of the
 # other owners, the rank's ZeRO-3 shard, the received ZeRO-3 shards), each stream holds the slices
 # of all buckets of the class back to back in bucket order, and the streams follow one another
-# inside one allocation, each starting on a multiple of ARENA_ALIGN bytes, an ODD number of
-# ARENA_ALIGN units after the start of the stream before it (streams that are read at the same
-# relative position should not lie a large power of two apart).
+# inside one allocation, each starting on a multiple of ARENA_ALIGN bytes.  The distance between the
+# starts of consecutive streams, in ARENA_ALIGN units, is the smallest that holds the earlier stream
+# and is congruent to r modulo M; (M, r) = ARENA_RULES[variant].  Variant 0 is "an odd number of
+# units" (streams that are read at the same relative position should not lie a large power of two
+# apart); the others exist because the best spacing depends on sizes and placement and is chosen by
+# measurement.  The table is part of the interface and therefore the same on both sides.
 # ---------------------------------------------------------------------------------------------
 ARENA_ALIGN = 2 << 20
+ARENA_RULES = ((2, 1), (1, 0), (2, 0), (16, 3), (16, 13), (64, 21), (64, 35), (64, 59))
 STREAM_GRAD, STREAM_MASTER, STREAM_M, STREAM_V, STREAM_PARAM_OUT, STREAM_RECV1, STREAM_SHARD3, STREAM_RECV3 = range(8)
 
 
@@ -270,8 +274,9 @@ def arena_streams(plan, cls, R, grad_bytes):
     return out
 
 
-def arena_layout(plan, cls, R, grad_bytes):
+def arena_layout(plan, cls, R, grad_bytes, variant=0):
     """(total_bytes, {(kind, index, layer): (byte_offset, bytes)}) for the class's buckets."""
+    modulus, residue = ARENA_RULES[variant]
     buckets = [b for b in plan["buckets"] if b["cls"] == cls]
     if not buckets:
         raise PlanError("the plan has no bucket of that class")
@@ -280,8 +285,8 @@ def arena_layout(plan, cls, R, grad_bytes):
     prev_start = None
     for kind, index, level, eb in arena_streams(plan, cls, R, grad_bytes):
         pos = round_up(pos, ARENA_ALIGN)
-        if prev_start is not None and ((pos - prev_start) // ARENA_ALIGN) % 2 == 0:
-            pos += ARENA_ALIGN                      # odd spacing between consecutive streams
+        while prev_start is not None and ((pos - prev_start) // ARENA_ALIGN) % modulus != residue:
+            pos += ARENA_ALIGN                      # next spacing that satisfies the variant's rule
         prev_start = pos
         for b in buckets:
             n = b["S1"] if level == 1 else b["S3"]

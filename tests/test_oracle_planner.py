@@ -381,3 +381,22 @@ def test_arena_layout_invariants_and_hand_values():
     assert sl[op.STREAM_M, 0, 0] == (26 * M, 16 * M) and sl[op.STREAM_V, 0, 0] == (43 * M, 16 * M)
     assert sl[op.STREAM_PARAM_OUT, 0, 0] == (60 * M, 8 * M) and sl[op.STREAM_SHARD3, 0, 0] == (69 * M, 8 * M)
     assert total == 77 * M
+    # the other variants: same streams and slices, only the spacing rule differs.  Hand values for the
+    # plan above (streams of 8 and 16 units): variant 1 packs them (8, 16, 16, 16, 8 -> starts 0, 8, 24, 40, 56, 64),
+    # variant 2 keeps even spacings as they are, variant 3 takes the next spacing congruent 3 modulo 16
+    # (8 -> 19, 16 -> 19), variant 7 the next congruent 59 modulo 64 (59 for both lengths)
+    def starts(variant):
+        tot, x = op.arena_layout(plan, 0, 1, 2, variant)
+        return [x[k, 0, 0][0] // M for k in (op.STREAM_GRAD, op.STREAM_MASTER, op.STREAM_M, op.STREAM_V,
+                                              op.STREAM_PARAM_OUT, op.STREAM_SHARD3)], tot
+    assert starts(1) == ([0, 8, 24, 40, 56, 64], 72 * M)
+    assert starts(2) == starts(1)
+    assert starts(3) == ([0, 19, 38, 57, 76, 95], 103 * M)
+    assert starts(7) == ([0, 59, 118, 177, 236, 295], 303 * M)
+    assert op.ARENA_RULES[0] == (2, 1)
+    for variant, (modulus, residue) in enumerate(op.ARENA_RULES):
+        st, tot = starts(variant)
+        sizes = [8, 16, 16, 16, 8, 8]
+        for a, b, n in zip(st, st[1:], sizes):
+            assert (b - a) % modulus == residue and n <= b - a < n + modulus      # the least spacing that fits the rule
+        assert tot == st[-1] * M + 8 * M
