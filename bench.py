@@ -45,6 +45,9 @@ def parse_args():
     ap.add_argument("--layout", default="arena", choices=["arena", "kinds"],
                     help="arena: the rank's streams in one allocation at the planner's offsets (default); kinds: one "
                          "allocation per stream kind")
+    ap.add_argument("--arena-variant", default="tune",
+                    help="layout variant of hzp_plan_arena (0..7), or 'tune': hzp_arena_tune picks it at set-up, "
+                         "before the buffers are filled (default)")
     ap.add_argument("--gather1-per-layer", action="store_true",
                     help="issue the level-1 gather as one call per layer instead of one call for all layers")
     ap.add_argument("--phases", default="fused,gather1,gather3",
@@ -60,13 +63,15 @@ class Workload:
     Layout "arena" (default): the rank's persistent streams (replica r's gradient slices, master,
     momentum, variance, bf16 output, received ZeRO-1 pieces, the ZeRO-3 shard, received shards) lie
     in ONE allocation at the offsets the planner gives (hzp_plan_arena / hzp_plan_arena_slice: every
-    stream on a 2 MiB boundary, the slices of all layer buckets back to back); only the gathered
+    stream on a 2 MiB boundary, the slices of all layer buckets back to back; the spacing variant is
+    chosen by hzp_arena_tune on the empty allocation unless `arena_variant` names one); only the gathered
     layer buckets (and a rotating pool's shards) are allocations of their own.  Layout "kinds": one
     allocation per stream kind, same order inside (the earlier default: 1-4 % slower on average and
     much less repeatable from process to process).  `separate=True` gives every slice its own
     allocation (slower again)."""
 
-    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False, l3_pool=0, layout="arena"):
+    def __init__(self, cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=False, l3_pool=0, layout="arena",
+                 arena_variant="tune"):
         """l3_pool > 0: the level-3 gather streams through a rotating pool (the cyclic buffers of
         Section 4.2): the received ZeRO-3 shards of only `l3_pool` layers and two destination buckets
         are resident, layer l using slot l % l3_pool and bucket l % 2.  For layer streams whose full
@@ -91,9 +96,17 @@ class Workload:
         big, big_off = None, 0
         if self.layout == "arena":
             A = hzp.HZP_ARENA_ALIGN
-            whole = torch.empty(self.plan.arena(0, self.R) + A, dtype=torch.uint8, device=dev)
+            tune = arena_variant == "tune"
+            variants = range(hzp.HZP_ARENA_VARIANTS) if tune else [int(arena_variant)]
+            nbytes = max(self.plan.arena(0, self.R, variant=v) for v in variants)
+            whole = torch.empty(nbytes + A, dtype=torch.uint8, device=dev)
             big_off = (-whole.data_ptr()) % A          # the arena starts on a multiple of HZP_ARENA_ALIGN
             big = self.arena_buffer = whole
+            self.arena_variant, self.arena_tune_seconds = (0 if tune else int(arena_variant)), None
+            if tune:                                   # set-up time: the allocation is still empty
+                self.plan.prepare()
+                self.arena_variant, self.arena_tune_seconds = self.plan.arena_tune(
+                    0, rank, self.R, whole.data_ptr() + big_off, nbytes)
 
         def stream_of(name):
             """(hzp stream, index) of an arena name, or None for buffers outside the planner's arena."""
@@ -121,7 +134,7 @@ class Workload:
             if separate:
                 t = torch.empty(n, dtype=dtype, device=dev)
             elif st is not None:
-                off, nbytes = self.plan.arena_slice(0, self.R, st[0], st[1], layer)
+                off, nbytes = self.plan.arena_slice(0, self.R, st[0], st[1], layer, variant=self.arena_variant)
                 t = big[big_off + off:big_off + off + nbytes].view(dtype)
                 assert t.numel() == n
                 arenas.setdefault(name, t)
@@ -587,7 +600,7 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
     # gather runs through a rotating pool of 8 layers of received shards and 2 destination buckets
     pool = 8 if cfg["name"] == "dense70b" and n_layers > 8 and not args.separate_allocations else 0
     w = Workload(cfg, n_layers, rank, torch, hzp, hzp_inputs, separate=args.separate_allocations, l3_pool=pool,
-                 layout=args.layout)
+                 layout=args.layout, arena_variant=args.arena_variant)
     w.l1_per_layer = args.gather1_per_layer
     phases = set(args.phases.split(","))
     stream = torch.cuda.Stream()
@@ -646,6 +659,9 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
         "fused_launches": fused_launches, "s1_total": w.s1_total, "p_total": w.p_total,
         "payload_params": w.payload_params, "n_layers": w.n_layers, "R": R, "z3": w.z3, "K": w.K,
         "l1_per_layer": w.l1_per_layer, "l3_pool": pool, "layout": w.layout,
+        "arena_variant": getattr(w, "arena_variant", None),
+        "arena_tune_GBps": ([round(fused_bytes / s / 1e9, 1) if s > 0 else None for s in w.arena_tune_seconds]
+                            if getattr(w, "arena_tune_seconds", None) else None),
     }
     return out
 
@@ -654,6 +670,8 @@ def workload_text(t):
     cfg = t["cfg"]
     where = {"arena": "the rank's streams in one allocation at the planner's offsets (hzp_plan_arena)",
              "kinds": "one allocation per stream kind", "separate": "one allocation per slice"}[t["layout"]]
+    if t["layout"] == "arena":
+        where += ", layout variant %d%s" % (t["arena_variant"], " chosen by hzp_arena_tune at set-up" if t["arena_tune_GBps"] else "")
     return ("%s: %d layer buckets, R=%d, Z3=%d, Z1=%d, A=%d, rank %d, %s; step = fused reduce+AdamW on the S1 shards "
             "(%d launches) + level-1 gather (%s) + level-3 gather per layer%s; `value` is shard parameters per second of "
             "the whole step, `fused_update` the metric's own kernel"
@@ -670,6 +688,7 @@ def triple(t):
                                                                "traffic", "traffic_key")}
     return {"workload": workload_text(t), "steps": t["steps"], "ms_per_step": round(t["ms_per_step"], 4),
             "shard_params_per_step": t["s1_total"],
+            "arena_variant": t["arena_variant"], "arena_tune_GBps": t["arena_tune_GBps"],
             "fused_update_params_per_s": t["s1_total"] / (t["fused_ms"] * 1e-3) if t["fused_ms"] > 0 else None,
             "fused": short(r.get("fused_adamw")), "gather1": short(r.get("gather_level1")),
             "gather3": short(r.get("gather_level3"))}
@@ -710,7 +729,8 @@ def main():
         "config": {"workload": workload_text(t),
                    "shard_params_per_step": w.s1_total, "padded_params": w.p_total,
                    "payload_params": w.payload_params, "padding_params": w.p_total - w.payload_params,
-                   "phases": sorted(t["phases"])},
+                   "phases": sorted(t["phases"]), "arena_variant": t["arena_variant"],
+                   "arena_tune_GBps": t["arena_tune_GBps"]},
         "fused_update_params_per_s": fused_pps,
         "fused_update_GBps": rooflines.get("fused_adamw", {}).get("achieved"),
         "roofline": dominant,
@@ -773,7 +793,7 @@ def main():
                 cmd.append("--gather1-per-layer")
             if args.separate_allocations:
                 cmd.append("--separate-allocations")
-            cmd += ["--layout", args.layout]
+            cmd += ["--layout", args.layout, "--arena-variant", args.arena_variant]
             res = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
             if res.returncode != 0:
                 print(res.stderr[-2000:], file=sys.stderr)

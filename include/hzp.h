@@ -190,33 +190,42 @@ hzp_status_t hzp_plan_bytes(const hzp_plan_t *plan, uint64_t *opt_bytes, uint64_
  * This library's: the rank's buffers are streams -- R gradient contributions, master, momentum,
  * variance, cast parameters, the received ZeRO-1 pieces of the K-1 other owners of its ZeRO-3
  * shard, that shard, the Z3-1 received ZeRO-3 shards -- in that order inside ONE allocation; every
- * stream starts on a multiple of HZP_ARENA_ALIGN bytes, an odd number of HZP_ARENA_ALIGN units
- * after the start of the stream before it, and holds the slices (S1 or S3 elements) of all
- * buckets of the class back to back in bucket order.  The caller allocates total_bytes once,
- * aligned to HZP_ARENA_ALIGN, and hands `base + byte_offset` to the entry points; every offset is a
- * multiple of 16.  Why one allocation: the fused update reads R+3 and writes 4 of these streams at
- * the same relative position, and how their addresses lie against one another moves its bandwidth
- * by several per cent; separate allocations land wherever the driver puts them (measured on MI355X
- * over 5 processes each, 7B-class share: 5.90-6.34 TB/s with one allocation per stream kind,
- * 6.46-6.52 with this arena; streams exactly 256 MiB apart: 5.96; even numbers of units apart: 1-2 %
- * below odd ones on average; a 4 KiB stagger between the streams: 6.1-6.2).
+ * stream starts on a multiple of HZP_ARENA_ALIGN bytes and holds the slices (S1 or S3 elements) of
+ * all buckets of the class back to back in bucket order.  The distance between the starts of
+ * consecutive streams, in units of HZP_ARENA_ALIGN, is the smallest one that holds the earlier
+ * stream and is congruent to r modulo M, where (M, r) is fixed by the layout variant:
+ *   variant 0: (2, 1) -- an odd number of units, the default;  1: (1, 0) -- no extra spacing;
+ *   2: (2, 0);  3: (16, 3);  4: (16, 13);  5: (64, 21);  6: (64, 35);  7: (64, 59).
+ * The caller allocates total_bytes once, aligned to HZP_ARENA_ALIGN, and hands `base + byte_offset`
+ * to the entry points; every offset is a multiple of 16.
+ * Why one allocation, and why variants: the fused update reads R+3 and writes 4 of these streams
+ * at the same relative position, and how their addresses lie against one another in physical
+ * memory moves its bandwidth by several per cent.  Separate allocations land wherever the driver
+ * puts them (measured on MI355X over 5 processes each, 7B-class share: 5.90-6.34 TB/s with one
+ * allocation per stream kind, 6.46-6.52 with this arena).  Inside one allocation the spacing
+ * decides: streams exactly 256 MiB apart 5.96 TB/s, an even number of units apart 1-9 % below odd
+ * ones on most shapes, a 4 KiB stagger between the streams 6.1-6.2.  Which spacing is best depends
+ * on the streams' sizes and on where the allocation lies (the same variant moved by 16 GiB inside
+ * a larger allocation: 6.46 -> 6.16 TB/s), so hzp_arena_tune measures it on the caller's allocation.
  *   cls, R, grad_dtype : class of the buckets, number of contributions (0 .. HZP_MAX_REPLICAS) and their
  *                        element type (an hzp_grad_dtype_t) -- they fix the streams and their sizes
+ *   variant            : 0 .. HZP_ARENA_VARIANTS-1
  *   stream, index      : an hzp_stream_t; index r < R for GRAD, k < K-1 for RECV1, j < Z3-1 for RECV3, else 0
  * Host-only integer work.  Errors: INVALID_ARG (NULL, unknown gradient type), RANGE (class without a
- * bucket, layer, stream, index), UNSUPPORTED (R too large; RECV1 when z3 does not divide z1).
+ * bucket, layer, stream, index, variant), UNSUPPORTED (R too large; RECV1 when z3 does not divide z1).
  * ------------------------------------------------------------------------------------------ */
 #define HZP_ARENA_ALIGN (2u << 20)
+#define HZP_ARENA_VARIANTS 8u
 typedef enum {
     HZP_STREAM_GRAD = 0, HZP_STREAM_MASTER = 1, HZP_STREAM_M = 2, HZP_STREAM_V = 3, HZP_STREAM_PARAM_OUT = 4,
     HZP_STREAM_RECV1 = 5, HZP_STREAM_SHARD3 = 6, HZP_STREAM_RECV3 = 7
 } hzp_stream_t;
 hzp_status_t hzp_plan_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
-                            uint64_t *total_bytes);
+                            uint32_t variant, uint64_t *total_bytes);
 /* Where bucket (layer, cls)'s slice of a stream lies in the arena, and its size in bytes. */
 hzp_status_t hzp_plan_arena_slice(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
-                                  uint32_t stream, uint32_t index, uint32_t layer, uint64_t *byte_offset,
-                                  uint64_t *bytes);
+                                  uint32_t variant, uint32_t stream, uint32_t index, uint32_t layer,
+                                  uint64_t *byte_offset, uint64_t *bytes);
 
 /* Static model-state memory per device of Section 4.1.1 for N parameters,
  *     M_hzp = 12N/Z1 + 4N/Z2 + 2N/Z3   bytes,
@@ -296,6 +305,31 @@ hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint3
                              uint32_t rank, const hzp_adamw_t *hyper, const void *const *grad_slices,
                              uint32_t R, float *const *master, float *const *m, float *const *v,
                              void *const *param_out, hipStream_t stream);
+
+/* Set-up time choice of the arena layout variant (see hzp_plan_arena) for the fused update of
+ * Section 4.1.2's optimizer step: runs hzp_adamw_shard over all layers of the class, with the
+ * streams placed by each variant whose total fits arena_bytes, four times per variant, timing the
+ * last three with events on `stream`, and returns the variant with the shortest time (variant 0
+ * unless another one is more than 0.5 % faster).  Call it once
+ * after allocating the arena and before filling it: its contents are overwritten (each variant's
+ * streams with ordinary non-zero values: all-zero gradients run 1-3 % faster than any others and hide
+ * differences between the variants) and it is all zero on return (hzp_arena_tune is not for graph
+ * capture).
+ *   arena, arena_bytes : DEVICE allocation, start on a multiple of HZP_ARENA_ALIGN; it must hold
+ *                        variant 0; to let every variant compete, allocate the largest of the
+ *                        variants' totals (at most 63 units per stream more than variant 1)
+ *   R                  : 1 .. HZP_MAX_REPLICAS contributions of the class's default gradient type
+ *   best_variant       : OUT
+ *   seconds            : OUT, HOST array of HZP_ARENA_VARIANTS, seconds per update of each variant
+ *                        (0 for a variant that does not fit), or NULL
+ * Blocks until the measurements are done; creates and destroys two events; allocates device memory
+ * only if hzp_plan_prepare was not called.  The variants lie a few per cent apart at most and a
+ * measurement repeats to a few tenths of a per cent, so two runs may pick different variants of
+ * nearly equal speed.
+ * Errors: INVALID_ARG (NULL, R == 0, arena too small for variant 0), RANGE (class, rank), ALIGN,
+ * UNSUPPORTED (R too large), and those of hzp_adamw_shard. */
+hzp_status_t hzp_arena_tune(const hzp_plan_t *plan, uint32_t cls, uint32_t rank, uint32_t R, void *arena,
+                            uint64_t arena_bytes, hipStream_t stream, uint32_t *best_variant, double *seconds);
 
 /* ------------------------------------------------------------------------------------------
  * Gather: the data-movement half of the two all-gathers of Section 4.1.2.

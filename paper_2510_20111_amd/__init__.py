@@ -5,7 +5,7 @@ this package is its thin ctypes binding.  Importing it requires the built librar
 """
 from .binding import (  # noqa: F401
     HZP_CLASS_BF16, HZP_CLASS_F32, HZP_GRAD_DEFAULT, HZP_GRAD_BF16, HZP_GRAD_F32, HZP_MAX_GROUP,
-    HZP_MAX_REPLICAS, HZP_ARENA_ALIGN,
+    HZP_MAX_REPLICAS, HZP_ARENA_ALIGN, HZP_ARENA_VARIANTS,
     HZP_STREAM_GRAD, HZP_STREAM_MASTER, HZP_STREAM_M, HZP_STREAM_V, HZP_STREAM_PARAM_OUT, HZP_STREAM_RECV1,
     HZP_STREAM_SHARD3, HZP_STREAM_RECV3,
     HZP_OK, HZP_ERR_INVALID_ARG, HZP_ERR_RANGE, HZP_ERR_UNSUPPORTED, HZP_ERR_ALIGN,

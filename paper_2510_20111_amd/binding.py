@@ -18,6 +18,7 @@ HZP_CLASS_BF16, HZP_CLASS_F32 = 0, 1
 HZP_GRAD_DEFAULT, HZP_GRAD_BF16, HZP_GRAD_F32 = 0, 1, 2
 HZP_MAX_REPLICAS, HZP_MAX_GROUP = 32, 64
 HZP_ARENA_ALIGN = 2 << 20
+HZP_ARENA_VARIANTS = 8
 (HZP_STREAM_GRAD, HZP_STREAM_MASTER, HZP_STREAM_M, HZP_STREAM_V, HZP_STREAM_PARAM_OUT, HZP_STREAM_RECV1,
  HZP_STREAM_SHARD3, HZP_STREAM_RECV3) = range(8)
 _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSUPPORTED",
@@ -25,7 +26,7 @@ _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSU
 
 EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_prepare", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
            "hzp_plan_rank", "hzp_plan_index", "hzp_plan_cover", "hzp_plan_shard", "hzp_plan_bytes",
-           "hzp_plan_arena", "hzp_plan_arena_slice",
+           "hzp_plan_arena", "hzp_plan_arena_slice", "hzp_arena_tune",
            "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_layer_static", "hzp_gather_layers", "hzp_gather_shard", "hzp_gather_tensor", "hzp_last_error",
            "hzp_memory_model", "hzp_choose_groups",
            "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_prefetch_ahead", "hzp_sched_acquire",
@@ -129,9 +130,11 @@ def _load():
     L.hzp_plan_shard.restype = ctypes.c_int
     L.hzp_plan_shard.argtypes = [vp, u32, u32, ctypes.c_int, u32, u64p, u64p]
     L.hzp_plan_arena.restype = ctypes.c_int
-    L.hzp_plan_arena.argtypes = [vp, u32, u32, u32, u64p]
+    L.hzp_plan_arena.argtypes = [vp, u32, u32, u32, u32, u64p]
     L.hzp_plan_arena_slice.restype = ctypes.c_int
-    L.hzp_plan_arena_slice.argtypes = [vp, u32, u32, u32, u32, u32, u32, u64p, u64p]
+    L.hzp_plan_arena_slice.argtypes = [vp, u32, u32, u32, u32, u32, u32, u32, u64p, u64p]
+    L.hzp_arena_tune.restype = ctypes.c_int
+    L.hzp_arena_tune.argtypes = [vp, u32, u32, u32, vp, ctypes.c_uint64, vp, ctypes.POINTER(u32), ctypes.POINTER(ctypes.c_double)]
     L.hzp_plan_bytes.restype = ctypes.c_int
     L.hzp_plan_bytes.argtypes = [vp, u64p, u64p, u64p]
     L.hzp_reduce_shard.restype = ctypes.c_int
@@ -270,18 +273,27 @@ class Plan:
         _check(_L.hzp_plan_shard(self.handle, layer, cls, level, rank, ctypes.byref(b), ctypes.byref(n)))
         return b.value, n.value
 
-    def arena(self, cls, R, grad_dtype=HZP_GRAD_DEFAULT):
+    def arena(self, cls, R, grad_dtype=HZP_GRAD_DEFAULT, variant=0):
         """Bytes of the one allocation that holds the rank's streams of class `cls`."""
         out = ctypes.c_uint64()
-        _check(_L.hzp_plan_arena(self.handle, cls, R, grad_dtype, ctypes.byref(out)))
+        _check(_L.hzp_plan_arena(self.handle, cls, R, grad_dtype, variant, ctypes.byref(out)))
         return out.value
 
-    def arena_slice(self, cls, R, stream, index, layer, grad_dtype=HZP_GRAD_DEFAULT):
+    def arena_slice(self, cls, R, stream, index, layer, grad_dtype=HZP_GRAD_DEFAULT, variant=0):
         """(byte_offset, bytes) of bucket (layer, cls)'s slice of a stream inside the arena."""
         off, n = ctypes.c_uint64(), ctypes.c_uint64()
-        _check(_L.hzp_plan_arena_slice(self.handle, cls, R, grad_dtype, stream, index, layer, ctypes.byref(off),
-                                       ctypes.byref(n)))
+        _check(_L.hzp_plan_arena_slice(self.handle, cls, R, grad_dtype, variant, stream, index, layer,
+                                       ctypes.byref(off), ctypes.byref(n)))
         return off.value, n.value
+
+    def arena_tune(self, cls, rank, R, arena, arena_bytes, stream=None):
+        """(best variant, [seconds per update of each variant, 0 where it does not fit]); `arena` is
+        a device pointer or a tensor.  Clears the arena."""
+        best = ctypes.c_uint32()
+        secs = (ctypes.c_double * HZP_ARENA_VARIANTS)()
+        _check(_L.hzp_arena_tune(self.handle, cls, rank, R, _addr(arena), arena_bytes, _stream(stream),
+                                 ctypes.byref(best), secs))
+        return best.value, list(secs)
 
     def bytes(self):
         o, g, p = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()

@@ -331,9 +331,18 @@ struct ArenaWalk {
 
 // Lays the streams out one after the other (each on a multiple of HZP_ARENA_ALIGN) and notes the one
 // asked for.  s1_bytes / s3_bytes: the class's ZeRO-1 / ZeRO-3 slices of all buckets, in elements.
-ArenaWalk walk_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_bytes, uint64_t s1_total,
-                     uint64_t s3_total, uint32_t want_stream, uint32_t want_index)
+// Spacing rule of each layout variant: the distance between the starts of consecutive streams, in
+// units of HZP_ARENA_ALIGN, is the smallest one that holds the earlier stream and is congruent to
+// `residue` modulo `modulus`.
+struct ArenaRule {
+    uint32_t modulus, residue;
+};
+const ArenaRule kArenaRules[HZP_ARENA_VARIANTS] = {{2, 1}, {1, 0}, {2, 0}, {16, 3}, {16, 13}, {64, 21}, {64, 35}, {64, 59}};
+
+ArenaWalk walk_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_bytes, uint32_t variant,
+                     uint64_t s1_total, uint64_t s3_total, uint32_t want_stream, uint32_t want_index)
 {
+    const ArenaRule rule = kArenaRules[variant];
     const uint32_t eb = cls == HZP_CLASS_F32 ? 4u : 2u;
     struct Kind {
         uint32_t stream, count, level, elem;
@@ -351,8 +360,10 @@ ArenaWalk walk_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t 
     for (const Kind &k : kinds)
         for (uint32_t i = 0; i < k.count; ++i) {
             uint64_t start = (end + HZP_ARENA_ALIGN - 1) / HZP_ARENA_ALIGN * HZP_ARENA_ALIGN;
-            // consecutive streams lie an odd number of alignment units apart
-            if (!first && ((start - last_start) / HZP_ARENA_ALIGN) % 2 == 0) start += HZP_ARENA_ALIGN;
+            if (!first) {
+                const uint64_t units = (start - last_start) / HZP_ARENA_ALIGN;
+                start += (rule.residue + rule.modulus - units % rule.modulus) % rule.modulus * HZP_ARENA_ALIGN;
+            }
             first = false;
             last_start = start;
             if (k.stream == want_stream && i == want_index) {
@@ -368,9 +379,11 @@ ArenaWalk walk_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t 
 }
 
 hzp_status_t arena_args(const char *who, const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
-                        uint32_t *grad_bytes, uint64_t *s1_total, uint64_t *s3_total)
+                        uint32_t variant, uint32_t *grad_bytes, uint64_t *s1_total, uint64_t *s3_total)
 {
     if (!plan) return fail(HZP_ERR_INVALID_ARG, "%s: NULL plan", who);
+    if (variant >= HZP_ARENA_VARIANTS)
+        return fail(HZP_ERR_RANGE, "%s: layout variant %u of %u", who, variant, HZP_ARENA_VARIANTS);
     if (cls > 1) return fail(HZP_ERR_RANGE, "%s: class %u", who, cls);
     if (grad_dtype > HZP_GRAD_F32) return fail(HZP_ERR_INVALID_ARG, "%s: unknown gradient type %u", who, grad_dtype);
     if (R > HZP_MAX_REPLICAS) return fail(HZP_ERR_UNSUPPORTED, "%s: R=%u exceeds %u", who, R, HZP_MAX_REPLICAS);
@@ -384,9 +397,9 @@ hzp_status_t arena_args(const char *who, const hzp_plan_t *plan, uint32_t cls, u
             any = true;
         }
     if (!any) return fail(HZP_ERR_RANGE, "%s: the plan has no bucket of class %u", who, cls);
-    // at most R + 4 + K + Z3 streams of at most 4 bytes x (a or c) each, plus the alignment gaps
+    // at most R + 4 + K + Z3 streams of at most 4 bytes x (a or c) each, plus the gaps (under 65 units each)
     const unsigned __int128 bound = ((unsigned __int128)R + 4 + plan->K + plan->z3) *
-                                    (4 * (unsigned __int128)(a > c ? a : c) + HZP_ARENA_ALIGN);
+                                    (4 * (unsigned __int128)(a > c ? a : c) + 65ull * HZP_ARENA_ALIGN);
     if (bound >> 63) return fail(HZP_ERR_UNSUPPORTED, "%s: the arena would exceed 2^63 bytes", who);
     *s1_total = a;
     *s3_total = c;
@@ -396,25 +409,25 @@ hzp_status_t arena_args(const char *who, const hzp_plan_t *plan, uint32_t cls, u
 }  // namespace
 
 extern "C" hzp_status_t hzp_plan_arena(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
-                                       uint64_t *total_bytes)
+                                       uint32_t variant, uint64_t *total_bytes)
 {
     if (!total_bytes) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_arena: NULL output");
     uint32_t gb = 0;
     uint64_t s1 = 0, s3 = 0;
-    hzp_status_t st = arena_args("hzp_plan_arena", plan, cls, R, grad_dtype, &gb, &s1, &s3);
+    hzp_status_t st = arena_args("hzp_plan_arena", plan, cls, R, grad_dtype, variant, &gb, &s1, &s3);
     if (st != HZP_OK) return st;
-    *total_bytes = walk_arena(plan, cls, R, gb, s1, s3, ~0u, 0).total;
+    *total_bytes = walk_arena(plan, cls, R, gb, variant, s1, s3, ~0u, 0).total;
     return HZP_OK;
 }
 
 extern "C" hzp_status_t hzp_plan_arena_slice(const hzp_plan_t *plan, uint32_t cls, uint32_t R, uint32_t grad_dtype,
-                                             uint32_t stream, uint32_t index, uint32_t layer, uint64_t *byte_offset,
-                                             uint64_t *bytes)
+                                             uint32_t variant, uint32_t stream, uint32_t index, uint32_t layer,
+                                             uint64_t *byte_offset, uint64_t *bytes)
 {
     if (!byte_offset || !bytes) return fail(HZP_ERR_INVALID_ARG, "hzp_plan_arena_slice: NULL output");
     uint32_t gb = 0;
     uint64_t s1 = 0, s3 = 0;
-    hzp_status_t st = arena_args("hzp_plan_arena_slice", plan, cls, R, grad_dtype, &gb, &s1, &s3);
+    hzp_status_t st = arena_args("hzp_plan_arena_slice", plan, cls, R, grad_dtype, variant, &gb, &s1, &s3);
     if (st != HZP_OK) return st;
     const BucketRec *b = find_bucket(plan, layer, cls);
     if (!b) return fail(HZP_ERR_RANGE, "hzp_plan_arena_slice: no bucket (layer %u, class %u)", layer, cls);
@@ -422,7 +435,7 @@ extern "C" hzp_status_t hzp_plan_arena_slice(const hzp_plan_t *plan, uint32_t cl
     if (stream == HZP_STREAM_RECV1 && plan->K == 0)
         return fail(HZP_ERR_UNSUPPORTED, "hzp_plan_arena_slice: z3=%u does not divide z1=%u: a ZeRO-3 shard has no "
                                          "whole ZeRO-1 owners", plan->z3, plan->z1);
-    const ArenaWalk w = walk_arena(plan, cls, R, gb, s1, s3, stream, index);
+    const ArenaWalk w = walk_arena(plan, cls, R, gb, variant, s1, s3, stream, index);
     if (!w.found) return fail(HZP_ERR_RANGE, "hzp_plan_arena_slice: stream %u has no index %u", stream, index);
     // the slices of the class's earlier buckets lie in front of this bucket's
     uint64_t before = 0;

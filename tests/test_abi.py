@@ -137,6 +137,20 @@ def test_adamw_argument_errors():
     assert _status(f, p, 0, 1, 0, 0, hy, one, 1, one, one, one, [0], stream=0) == hzp.HZP_ERR_INVALID_ARG
 
 
+def test_arena_tune_argument_errors_before_any_gpu_call():
+    p = _plan()
+    f = p.arena_tune
+    big = 1 << 30
+    base = hzp.HZP_ARENA_ALIGN * 16
+    assert _status(f, 0, 0, 1, 0, big, stream=0) == hzp.HZP_ERR_INVALID_ARG            # NULL arena
+    assert _status(f, 2, 0, 1, base, big, stream=0) == hzp.HZP_ERR_RANGE               # class
+    assert _status(f, 0, 99, 1, base, big, stream=0) == hzp.HZP_ERR_RANGE              # rank
+    assert _status(f, 0, 0, 0, base, big, stream=0) == hzp.HZP_ERR_INVALID_ARG         # R == 0
+    assert _status(f, 0, 0, 33, base, big, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+    assert _status(f, 0, 0, 1, base + 4096, big, stream=0) == hzp.HZP_ERR_ALIGN
+    assert _status(f, 0, 0, 1, base, p.arena(0, 1) - 1, stream=0) == hzp.HZP_ERR_INVALID_ARG   # variant 0 does not fit
+
+
 def test_gather_argument_errors():
     p = _plan()
     f = hzp.hzp_gather_layer

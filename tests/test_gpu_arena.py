@@ -1,0 +1,120 @@
+"""GPU tests of the arena layout: the tuner's choice among the layout variants, and the fused update
+on streams carved from one allocation at the planner's offsets, against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import hzp_inputs
+import paper_2510_20111_amd as hzp
+from oracle import numeric as on
+from oracle import planner as op
+
+from gpu_util import DEV, assert_cast_of, assert_close_f32, oracle_plan, payload_ranges, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+HP = hzp_inputs.ADAMW
+A = hzp.HZP_ARENA_ALIGN
+STREAMS = {"p": hzp.HZP_STREAM_MASTER, "m": hzp.HZP_STREAM_M, "v": hzp.HZP_STREAM_V, "o": hzp.HZP_STREAM_PARAM_OUT}
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def make():
+    # three layers of two tensors; S1 = 1.2-1.6 M elements, so a bf16 stream spans 4 units of 2 MiB
+    # and an fp32 stream 8: every variant's spacing rule has something to do
+    desc = dict(tensors_per_layer=[2, 2, 2], tensor_numel=[3000000, 1800000, 2500000, 2300017, 4100000, 2200000])
+    align, z3, z1, R = 128, 2, 4, 3
+    oplan = oracle_plan(desc, align, z3, z1)
+    plan = hzp.hzp_plan(desc["tensors_per_layer"], desc["tensor_numel"], align, z3, z1)
+    return desc, oplan, plan, R
+
+
+def aligned_arena(nbytes):
+    whole = torch.empty(nbytes + A, dtype=torch.uint8, device=DEV)
+    off = (-whole.data_ptr()) % A
+    return whole, whole[off:off + nbytes]
+
+
+def test_tuner_times_every_variant_that_fits_and_leaves_zeros():
+    say("arena tuner: all variants fit")
+    desc, oplan, plan, R = make()
+    rank = 1
+    totals = [plan.arena(0, R, variant=v) for v in range(hzp.HZP_ARENA_VARIANTS)]
+    assert totals == [op.arena_layout(oplan, 0, R, 2, v)[0] for v in range(hzp.HZP_ARENA_VARIANTS)]
+    whole, arena = aligned_arena(max(totals))
+    arena.fill_(0x5A)
+    best, secs = plan.arena_tune(0, rank, R, arena, arena.numel())
+    assert 0 <= best < hzp.HZP_ARENA_VARIANTS
+    assert all(s > 0 for s in secs)
+    # the fastest one, unless that is not more than 0.5 % faster than the default
+    assert (best == 0 and min(secs) >= 0.995 * secs[0]) or (secs[best] == min(secs) and secs[best] < 0.995 * secs[0])
+    assert not arena.any().item()                          # cleared on return
+    say("arena tuner: only the smallest variants fit")
+    small = totals[0]
+    whole2, arena2 = aligned_arena(small)
+    best2, secs2 = plan.arena_tune(0, rank, R, arena2, small)
+    for v in range(hzp.HZP_ARENA_VARIANTS):
+        assert (secs2[v] > 0) == (totals[v] <= small), (v, secs2, totals)
+    fit = [s for s in secs2 if s > 0]
+    assert totals[best2] <= small
+    assert (best2 == 0 and min(fit) >= 0.995 * secs2[0]) or (secs2[best2] == min(fit) and secs2[best2] < 0.995 * secs2[0])
+    assert not arena2.any().item()
+
+
+@pytest.mark.parametrize("variant", [0, 3, 7])
+def test_fused_update_on_arena_slices_matches_the_oracle(variant):
+    """Two steps with every stream at the planner's offset inside one allocation; the gaps between the
+    streams stay untouched."""
+    say("fused update on an arena, variant", variant)
+    desc, oplan, plan, R = make()
+    rank = 2
+    total, slices = op.arena_layout(oplan, 0, R, 2, variant)
+    assert plan.arena(0, R, variant=variant) == total
+    whole, arena = aligned_arena(total)
+    arena.zero_()
+    n_layers = oplan["n_layers"]
+
+    def view(kind, index, layer, dtype):
+        off, nbytes = plan.arena_slice(0, R, kind, index, layer, variant=variant)
+        assert (off, nbytes) == slices[kind, index, layer]
+        return arena[off:off + nbytes].view(dtype)
+
+    dev = {l: dict(g=[view(hzp.HZP_STREAM_GRAD, r, l, torch.int16) for r in range(R)],
+                   p=view(STREAMS["p"], 0, l, torch.float32), m=view(STREAMS["m"], 0, l, torch.float32),
+                   v=view(STREAMS["v"], 0, l, torch.float32), o=view(STREAMS["o"], 0, l, torch.int16))
+           for l in range(n_layers)}
+    ora = {}
+    for l in range(n_layers):
+        b = op.find_bucket(oplan, l, 0)
+        beg, n = op.shard_range(oplan, b, 1, rank)
+        p = np.ascontiguousarray(hzp_inputs.master_bucket(9, l, b["P"], payload_ranges(oplan, b), 0)[beg:beg + n])
+        ora[l] = dict(p=p.copy(), m=np.zeros(n, np.float32), v=np.zeros(n, np.float32))
+        dev[l]["p"].copy_(to_dev(p))
+    touched = torch.zeros(arena.numel(), dtype=torch.bool, device=DEV)
+    for off, nbytes in slices.values():
+        touched[off:off + nbytes] = True
+    for t in (1, 2):
+        hy = hzp.adamw_hyper(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], 1.0 / R, t)
+        for l in range(n_layers):
+            b = op.find_bucket(oplan, l, 0)
+            beg, n = op.shard_range(oplan, b, 1, rank)
+            gs = [np.ascontiguousarray(hzp_inputs.grad_bucket(9, t, l, r, b["P"], payload_ranges(oplan, b), 1e-3, 0)[beg:beg + n])
+                  for r in range(R)]
+            for r in range(R):
+                dev[l]["g"][r].copy_(to_dev(gs[r]))
+            st = ora[l]
+            st["out"] = on.adamw(on.reduce(gs, scale=1.0 / R), st["p"], st["m"], st["v"], step=t, wd_mult=None,
+                                 out_bf16=True, **HP)
+        hzp.hzp_adamw_shard(plan, 0, n_layers, 0, rank, hy, [g for l in range(n_layers) for g in dev[l]["g"]], R,
+                            [dev[l]["p"] for l in range(n_layers)], [dev[l]["m"] for l in range(n_layers)],
+                            [dev[l]["v"] for l in range(n_layers)], [dev[l]["o"] for l in range(n_layers)])
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            tag = "variant %d step %d layer %d" % (variant, t, l)
+            for key in ("p", "m", "v"):
+                assert_close_f32(to_host(dev[l][key], np.float32), ora[l][key], tag + " " + key, key)
+            assert_cast_of(to_host(dev[l]["o"], np.uint16), to_host(dev[l]["p"], np.float32), tag + " bf16")
+        assert not arena[~touched].any().item(), "a gap between the streams was written"

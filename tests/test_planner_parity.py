@@ -155,9 +155,10 @@ def test_choose_groups_matches_the_oracle():
 
 # ------------------------------------------------------------------ arena layout
 
-@given(desc=descriptors(), R=st.integers(0, 32), gd=st.sampled_from([0, 1, 2]))
-@settings(max_examples=120, deadline=None)
-def test_arena_layout_matches_the_oracle(desc, R, gd):
+@given(desc=descriptors(), R=st.integers(0, 32), gd=st.sampled_from([0, 1, 2]),
+       variant=st.integers(0, hzp.HZP_ARENA_VARIANTS - 1))
+@settings(max_examples=160, deadline=None)
+def test_arena_layout_matches_the_oracle(desc, R, gd, variant):
     oplan = op.make_plan(**desc)
     plan = hzp.hzp_plan(**desc)
     for cls in (0, 1):
@@ -168,10 +169,10 @@ def test_arena_layout_matches_the_oracle(desc, R, gd):
             assert e.value.status == hzp.HZP_ERR_RANGE
             continue
         gb = (4 if cls == 1 else 2) if gd == 0 else (4 if gd == 2 else 2)
-        total, slices = op.arena_layout(oplan, cls, R, gb)
-        assert plan.arena(cls, R, gd) == total
+        total, slices = op.arena_layout(oplan, cls, R, gb, variant)
+        assert plan.arena(cls, R, gd, variant) == total
         for (kind, index, layer), want in slices.items():
-            assert plan.arena_slice(cls, R, kind, index, layer, gd) == want, (kind, index, layer)
+            assert plan.arena_slice(cls, R, kind, index, layer, gd, variant) == want, (kind, index, layer)
         # indices one past the end of each stream are refused
         for kind, count in ((hzp.HZP_STREAM_GRAD, R), (hzp.HZP_STREAM_MASTER, 1), (hzp.HZP_STREAM_RECV3, oplan["z3"] - 1)):
             with pytest.raises(hzp.HzpError) as e:
@@ -199,8 +200,14 @@ def test_arena_argument_errors():
     assert status(plan.arena_slice, 0, 1, 8, 0, 0) == hzp.HZP_ERR_RANGE          # unknown stream
     assert status(plan.arena_slice, 1, 1, 0, 0, 1) == hzp.HZP_ERR_RANGE          # layer 1 has no fp32 bucket
     assert status(plan.arena_slice, 0, 1, 0, 0, 2) == hzp.HZP_ERR_RANGE          # no layer 2
+    assert len(op.ARENA_RULES) == hzp.HZP_ARENA_VARIANTS
+    assert status(plan.arena, 0, 1, 0, hzp.HZP_ARENA_VARIANTS) == hzp.HZP_ERR_RANGE
+    assert status(plan.arena_slice, 0, 1, 0, 0, 0, 0, hzp.HZP_ARENA_VARIANTS) == hzp.HZP_ERR_RANGE
     huge = hzp.hzp_plan([1] * 60000, [1 << 40] * 60000, align=8, z3=1, z1=1)   # 6.6e16 elements in all
     assert status(huge.arena, 0, 32) == hzp.HZP_ERR_UNSUPPORTED                # 37 streams of 4 bytes each pass 2^63
     # 5 streams (master, m, v, cast parameters, ZeRO-3 shard), each an even number of 2 MiB units long: one more
     # unit between consecutive streams
     assert huge.arena(0, 0) == 60000 * (1 << 40) * (4 * 3 + 2 + 2) + 4 * hzp.HZP_ARENA_ALIGN
+    assert huge.arena(0, 0, variant=1) == 60000 * (1 << 40) * (4 * 3 + 2 + 2)   # variant 1 adds no spacing
+    # variant 7: spacings congruent 59 modulo 64 units; the streams are multiples of 64 units long
+    assert huge.arena(0, 0, variant=7) == 60000 * (1 << 40) * (4 * 3 + 2 + 2) + 4 * 59 * hzp.HZP_ARENA_ALIGN
