@@ -53,7 +53,7 @@ def parse_args():
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
-                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,prereduced,perlayer,freegroups,overlap")
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,prereduced,perlayer,freegroups,inplace,notinplace,overlap")
     return ap.parse_args()
 
 
@@ -208,6 +208,20 @@ class Workload:
                            for l in range(n_layers)]
 
 
+def add_inplace_arrays(w):
+    hzp = w._hzp
+    k = w.plan.rank(w.rank)[1]
+    own, srcs = [], []
+    for l, kept in enumerate(w.keep):
+        owners, shard3 = kept[5], kept[6]
+        s1 = w.buckets[l].s1
+        piece = shard3[k * s1:(k + 1) * s1]
+        own.append(piece)
+        srcs += [piece if kk == k else owners[kk] for kk in range(w.K)]
+    w.inplace_keep = own
+    w.inplace_o, w.inplace_l1 = hzp.ptr_array(own), hzp.ptr_array(srcs)
+
+
 def add_secondary_buffers(w, phases):
     """Buffers of the secondary rows (allocated only when those phases are asked for):
     `unpack`: level-3 gather into unpadded per-tensor buffers; `reduce`: standalone fp32
@@ -269,7 +283,15 @@ def add_secondary_buffers(w, phases):
 
 def run_secondary(w, hzp, stream, phase):
     s = stream.cuda_stream
-    if phase == "perlayer":
+    if phase in ("inplace", "notinplace"):
+        # the update and the post-step gather, the update writing the rank's bf16 parameters straight into
+        # piece k of its ZeRO-3 shard (that piece is then not copied by the gather) -- or not
+        a = w.cfg["adamw"]
+        hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], w.cfg["grad_scale"], 1)
+        o_arr, l1_src = (w.inplace_o, w.inplace_l1) if phase == "inplace" else (w.o_arr, w.l1_all[0])
+        hzp.hzp_adamw_shard(w.plan, 0, w.n_layers, 0, w.rank, hy, w.g_arr, w.R, w.p_arr, w.m_arr, w.v_arr, o_arr, stream=s)
+        hzp.hzp_gather_layers(w.plan, 0, w.n_layers, 0, 1, l1_src, w.K, w.l1_all[1], stream=s)
+    elif phase == "perlayer":
         a = w.cfg["adamw"]
         hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], w.cfg["grad_scale"], 1)
         for l, g, p, m, v, o in w.layer_args:
@@ -646,9 +668,9 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
             rooflines["gather_level1"] = roof("concat_kernel (K=%d x S1 -> S3)" % w.K, g1_bytes, g1_ms,
                                               w.n_layers, "concat_l1_%s" % cfg["name"])
         else:
-            per_launch = min(40, 320 // w.K)        # layers one launch of the layer-range gather holds
+            pieces = w.n_layers * w.K               # one launch of the layer-range gather holds 192 pieces
             rooflines["gather_level1"] = roof("concat_layers_kernel (all layers, K=%d x S1 -> S3)" % w.K, g1_bytes,
-                                              g1_ms, -(-w.n_layers // per_launch), "concat_layers_l1_%s" % cfg["name"])
+                                              g1_ms, -(-pieces // 192), "concat_layers_l1_%s" % cfg["name"])
     if "gather3" in phases:
         rooflines["gather_level3"] = roof("concat_kernel (Z3=%d x S3 -> P)" % w.z3, g3_bytes, g3_ms,
                                           w.n_layers, "concat_l3_%s" % cfg["name"])
@@ -758,21 +780,27 @@ def main():
         result["scheduler_overlap"] = overlap_probe(w, hzp, torch, stream)
     if secondary:
         add_secondary_buffers(w, secondary)
+        if "inplace" in secondary:
+            add_inplace_arrays(w)
         torch.cuda.synchronize()        # the new buffers were filled on the default stream
         result["secondary"] = {}
         for phase in secondary:
             ms = time_secondary(w, hzp, torch, stream, phase, args.steps, args.warmup)
             nbytes = {"unpack": lambda: 4 * w.payload_total, "reduce": lambda: (2 * R + 4) * w.s3_total,
                       "accumulate": lambda: (4 * R + 8) * w.s3_total,
+                      "inplace": lambda: fused_bytes + 4 * w.s1_total * (w.K - 1),
+                      "notinplace": lambda: fused_bytes + 4 * w.s1_total * w.K,
                       "perlayer": lambda: fused_bytes, "freegroups": lambda: 4 * w.free_s3_total,
                       "prereduced": lambda: 30 * w.s1_total}[phase]()
             kname = {"unpack": "unpack_kernel<2>", "reduce": "reduce_kernel<bf16,R=%d>" % R,
                      "accumulate": "reduce_kernel<f32,R=%d,accumulate>" % R,
+                     "inplace": "fused update writing into the ZeRO-3 shard + level-1 gather of the other %d pieces" % (w.K - 1),
+                     "notinplace": "fused update + level-1 gather of all %d pieces" % w.K,
                      "perlayer": "fused_adamw_kernel<R=%d,bf16>, one call per layer" % R,
                      "prereduced": "fused_adamw_kernel<R=1,f32 gradient> (update from a reduced fp32 shard)",
                      "freegroups": "concat_ranges_kernel (Z1=%d over Z3=%d: ZeRO-3 shard from partial owners)"
                                    % (getattr(w, "free_z1", 0), w.z3)}[phase]
-            launches = fused_launches if phase == "prereduced" else w.n_layers
+            launches = fused_launches if phase == "prereduced" else 1 if phase in ("inplace", "notinplace") else w.n_layers
             result["secondary"][phase] = roof(kname, nbytes, ms, launches, "%s_%s" % (phase, cfg["name"]))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, torch, np)

@@ -345,8 +345,12 @@ hzp_status_t hzp_arena_tune(const hzp_plan_t *plan, uint32_t cls, uint32_t rank,
  *                NULL at level 3 when tensor_out is given
  *   tensor_out : level 3 only, may be NULL; host array [n_tensors of the bucket] of device
  *                pointers, each to numel_t elements, element-aligned only
- * At least one output is required; outputs must not overlap inputs.  With both outputs the shards
- * are read twice (one copy kernel per output).
+ * At least one output is required.  A shard may already lie in place: shard_ptrs[s] equal to the
+ * address of piece s inside bucket_out (bucket_out + s * shard bytes) -- the case of a rank whose
+ * update wrote its parameters straight into its ZeRO-3 shard -- is not copied and costs nothing; this
+ * holds for hzp_gather_layers and the scheduler's gathers as well.  Any other overlap of outputs and
+ * inputs is not detected and gives undefined contents.  With both outputs the shards are read twice
+ * (one copy kernel per output).
  * Errors: INVALID_ARG (n_shards mismatch, no output, tensor_out at level 1), RANGE, UNSUPPORTED
  * (more than HZP_MAX_GROUP shards; level 1 on a plan whose z3 does not divide z1 -- use
  * hzp_gather_shard), ALIGN, NOMEM, HIP.

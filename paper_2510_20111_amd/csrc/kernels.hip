@@ -431,7 +431,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) v
 // grid = (wavefront tiles per shard, number of shards).
 // ---------------------------------------------------------------------------------------
 struct ConcatArgs {
-    const void *src[HZP_MAX_GROUP];
+    const void *src[HZP_MAX_GROUP];     // the pieces that are copied (one that already lies in place is left out)
+    uint8_t slot[HZP_MAX_GROUP];        // position of each of them in the output
     u32x4 *dst;
     uint32_t vec_per_shard;
 };
@@ -445,30 +446,29 @@ __global__ __launch_bounds__(kWave) void concat_kernel(const ConcatArgs a)
     const uint32_t vec = blockIdx.x * kWave + threadIdx.x;
     if (vec >= a.vec_per_shard) return;
     const u32x4 val = ld_stream(reinterpret_cast<const u32x4 *>(a.src[s]) + vec);
-    u32x4 *dst = a.dst + (size_t)s * a.vec_per_shard + vec;
+    u32x4 *dst = a.dst + (size_t)a.slot[s] * a.vec_per_shard + vec;
     st_writethrough(dst, val);
 }
 
 // The same copy for the buckets of many layers in one launch (the post-step gather runs for all
 // layers at once; 34 launches of 16 us each leave the memory system idle between them).
-// grid = (tiles of the longest piece, pieces of all layers); piece s belongs to layer s / per_layer.
-constexpr int kLayersPieceCap = 320;
-constexpr int kLayersCap = 40;
+// grid = (tiles of the longest piece, pieces to copy of all layers); a piece that already lies in
+// place is left out of the list.  Everything a workgroup needs is indexed by its piece alone (one
+// round of scalar loads before the first vector load).
+constexpr int kLayersPieceCap = 192;
 struct ConcatLayersArgs {
     const void *src[kLayersPieceCap];
-    u32x4 *dst[kLayersCap];
-    uint32_t nvec[kLayersCap];      // vectors per piece of the layer
-    uint32_t per_layer;             // pieces per layer
+    u32x4 *dst[kLayersPieceCap];            // where the piece goes
+    uint32_t nvec[kLayersPieceCap];         // its length in 16-byte vectors
 };
+static_assert(sizeof(ConcatLayersArgs) <= 4096, "kernel arguments");
 __global__ __launch_bounds__(kWave) void concat_layers_kernel(const ConcatLayersArgs a)
 {
     const uint32_t s = blockIdx.y;
-    const uint32_t layer = s / a.per_layer, k = s - layer * a.per_layer;
-    const uint32_t n = a.nvec[layer];
     const uint32_t vec = blockIdx.x * kWave + threadIdx.x;
-    if (vec >= n) return;
+    if (vec >= a.nvec[s]) return;
     const u32x4 val = ld_stream(reinterpret_cast<const u32x4 *>(a.src[s]) + vec);
-    st_writethrough(a.dst[layer] + (size_t)k * n + vec, val);
+    st_writethrough(a.dst[s] + vec, val);
 }
 
 // The same copy for pieces of different lengths (a ZeRO-3 shard rebuilt from whole and partial
@@ -775,10 +775,16 @@ hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t 
     const uint64_t nvec = bytes_per_shard / 16;
     if (nvec > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layer: shard larger than 64 GiB");
     ConcatArgs a{};
-    for (uint32_t s = 0; s < n_shards; ++s) a.src[s] = srcs[s];
+    uint32_t listed = 0;
+    for (uint32_t s = 0; s < n_shards; ++s) {
+        if (srcs[s] == static_cast<const char *>(dst) + (size_t)s * bytes_per_shard) continue;     // in place
+        a.src[listed] = srcs[s];
+        a.slot[listed++] = (uint8_t)s;
+    }
+    if (listed == 0) return HZP_OK;
     a.dst = reinterpret_cast<u32x4 *>(dst);
     a.vec_per_shard = (uint32_t)nvec;
-    const dim3 grid((uint32_t)((nvec + kWave - 1) / kWave), n_shards), block(kWave);
+    const dim3 grid((uint32_t)((nvec + kWave - 1) / kWave), listed), block(kWave);
     hipLaunchKernelGGL(concat_kernel, grid, block, 0, stream, a);
     return check_launch("hzp_gather_layer");
 }
@@ -786,23 +792,43 @@ hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t 
 hzp_status_t launch_concat_layers(const void *const *srcs, uint32_t per_layer, const uint64_t *bytes_per_piece,
                                   void *const *dsts, uint32_t n_layers, hipStream_t stream)
 {
-    const uint32_t layers_per_launch = std::min<uint32_t>(kLayersCap, kLayersPieceCap / per_layer);
-    for (uint32_t l0 = 0; l0 < n_layers; l0 += layers_per_launch) {
-        const uint32_t cnt = std::min(layers_per_launch, n_layers - l0);
+    // the pieces that have to move, layer after layer
+    struct Item {
+        const void *src;
+        char *dst;
+        uint64_t nvec;
+    };
+    std::vector<Item> items;
+    try {
+        items.reserve((size_t)n_layers * per_layer);
+    } catch (const std::bad_alloc &) {
+        return fail(HZP_ERR_NOMEM, "hzp_gather_layers: out of host memory");
+    }
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const uint64_t bytes = bytes_per_piece[l];
+        if (bytes / 16 > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layers: shard larger than 64 GiB");
+        if (bytes == 0) continue;
+        for (uint32_t k = 0; k < per_layer; ++k) {
+            const void *src = srcs[(size_t)l * per_layer + k];
+            char *dst = static_cast<char *>(dsts[l]) + (size_t)k * bytes;
+            if (src != dst) items.push_back({src, dst, bytes / 16});      // else the piece lies in place
+        }
+    }
+    // launches of equal numbers of pieces
+    const size_t launches = (items.size() + kLayersPieceCap - 1) / kLayersPieceCap;
+    for (size_t i = 0, done = 0; i < launches; ++i) {
+        const size_t cnt = (items.size() - done + (launches - i) - 1) / (launches - i);
         ConcatLayersArgs a{};
         uint64_t longest = 0;
-        for (uint32_t l = 0; l < cnt; ++l) {
-            const uint64_t nvec = bytes_per_piece[l0 + l] / 16;
-            if (nvec > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layers: shard larger than 64 GiB");
-            a.nvec[l] = (uint32_t)nvec;
-            a.dst[l] = reinterpret_cast<u32x4 *>(dsts[l0 + l]);
-            longest = std::max(longest, nvec);
-            for (uint32_t k = 0; k < per_layer; ++k)
-                a.src[l * per_layer + k] = srcs[(size_t)(l0 + l) * per_layer + k];
+        for (size_t s = 0; s < cnt; ++s) {
+            const Item &it = items[done + s];
+            a.src[s] = it.src;
+            a.dst[s] = reinterpret_cast<u32x4 *>(it.dst);
+            a.nvec[s] = (uint32_t)it.nvec;
+            longest = std::max(longest, it.nvec);
         }
-        a.per_layer = per_layer;
-        if (longest == 0) continue;
-        const dim3 grid((uint32_t)((longest + kWave - 1) / kWave), cnt * per_layer), block(kWave);
+        done += cnt;
+        const dim3 grid((uint32_t)((longest + kWave - 1) / kWave), (uint32_t)cnt), block(kWave);
         hipLaunchKernelGGL(concat_layers_kernel, grid, block, 0, stream, a);
         hzp_status_t st = check_launch("hzp_gather_layers");
         if (st != HZP_OK) return st;

@@ -544,6 +544,52 @@ def test_update_can_write_straight_into_the_zero3_shard():
     assert (got[:k * S1] == 0x7FC1).all() and (got[(k + 1) * S1:] == 0x7FC1).all()
 
 
+@pytest.mark.parametrize("level", [1, 3])
+def test_gather_leaves_a_piece_that_lies_in_place(level):
+    """The rank's own piece may already be where the gather would put it (the update wrote it there):
+    that piece is not copied, the others are, in one layer and in a range of layers; all pieces in place
+    launch nothing."""
+    say("gather with a piece in place, level", level)
+    desc = hzp_inputs.irregular_desc(12, seed=91, max_numel=90000, tensors_per_layer=2, f32_every=0)
+    desc = dict(desc, tensor_wd_mult=None, tensor_class=None)
+    z3, z1 = 4, 16
+    oplan, plan = oracle_plan(desc, 8, z3, z1), lib_plan(desc, 8, z3, z1)
+    n_shards = oplan["K"] if level == 1 else z3
+    rng = np.random.default_rng(5)
+    n_layers = oplan["n_layers"]
+    for own in (0, 2, n_shards - 1):
+        srcs, dsts, wants, keep = [], [], [], []
+        for layer in range(n_layers):
+            b = op.find_bucket(oplan, layer, 0)
+            n = b["S1"] if level == 1 else b["S3"]
+            pieces = [rng.integers(0, 65536, n, dtype=np.uint16) for _ in range(n_shards)]
+            whole, out = guarded(n * n_shards, torch.int16)
+            out.fill_(0x1111)
+            out[own * n:(own + 1) * n].copy_(to_dev(pieces[own]))          # already in place
+            dev = [out[own * n:(own + 1) * n] if s == own else to_dev(pieces[s]) for s in range(n_shards)]
+            srcs += dev
+            dsts.append(out)
+            keep.append(whole)
+            wants.append(on.gather_concat(pieces))
+        # one layer at a time for the first half, one call for the rest
+        half = n_layers // 2
+        for layer in range(half):
+            hzp.hzp_gather_layer(plan, layer, 0, level, srcs[layer * n_shards:(layer + 1) * n_shards], dsts[layer], None)
+        hzp.hzp_gather_layers(plan, half, n_layers, 0, level, srcs[half * n_shards:], n_shards, dsts[half:])
+        torch.cuda.synchronize()
+        for layer in range(n_layers):
+            assert np.array_equal(to_host(dsts[layer], np.uint16), wants[layer]), (own, layer)
+            assert guards_intact(keep[layer], dsts[layer].numel())
+    # every piece in place: nothing to do, nothing changes
+    b = op.find_bucket(oplan, 0, 0)
+    n = b["S1"] if level == 1 else b["S3"]
+    out = to_dev(rng.integers(0, 65536, n * n_shards, dtype=np.uint16))
+    before = to_host(out, np.uint16).copy()
+    hzp.hzp_gather_layer(plan, 0, 0, level, [out[s * n:(s + 1) * n] for s in range(n_shards)], out, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(out, np.uint16), before)
+
+
 def test_gather_one_parameter_at_a_time():
     """Per-parameter gather (the granularity Section 4.2 prefers): every tensor of an irregular plan
     rebuilt on its own from the shards it meets -- the other shard entries are NULL -- into an
