@@ -53,7 +53,7 @@ def parse_args():
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
-                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,prereduced,perlayer,freegroups,inplace,notinplace,overlap")
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,prereduced,perlayer,freegroups,inplace,notinplace,graph,overlap")
     return ap.parse_args()
 
 
@@ -326,6 +326,31 @@ def time_secondary(w, hzp, torch, stream, phase, steps, warmup):
     e1.record(stream)
     stream.synchronize()
     return e0.elapsed_time(e1) / steps
+
+
+def graph_probe(w, hzp, torch, stream, phases, steps, warmup):
+    """Secondary row: the whole step captured once into a HIP graph and replayed, against the same step
+    issued call by call -- what the launch-bound workloads (many small launches per step) gain.  The plan's
+    device tables exist (hzp_plan_prepare), so no call of the step allocates or copies."""
+    w.plan.prepare()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        run_step(w, hzp, 1, torch.cuda.current_stream(), phases)
+    torch.cuda.synchronize()
+    out = {}
+    for name, fn in (("eager", lambda: run_step(w, hzp, 1, stream, phases)), ("graph", g.replay)):
+        with torch.cuda.stream(stream):
+            for _ in range(warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(steps):
+                fn()
+            e1.record(stream)
+        stream.synchronize()
+        out[name + "_ms_per_step"] = round(e0.elapsed_time(e1) / steps, 4)
+    return out
 
 
 def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
@@ -778,6 +803,9 @@ def main():
     if "overlap" in secondary:
         secondary.remove("overlap")
         result["scheduler_overlap"] = overlap_probe(w, hzp, torch, stream)
+    if "graph" in secondary:
+        secondary.remove("graph")
+        result["graph_replay"] = graph_probe(w, hzp, torch, stream, t["phases"], max(args.steps, 20), args.warmup)
     if secondary:
         add_secondary_buffers(w, secondary)
         if "inplace" in secondary:
