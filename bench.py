@@ -53,7 +53,7 @@ def parse_args():
     ap.add_argument("--phases", default="fused,gather1,gather3",
                     help="comma list of the step's phases to run (profiling aid)")
     ap.add_argument("--secondary", default="",
-                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,prereduced,perlayer,freegroups,inplace,notinplace,graph,overlap")
+                    help="comma list of secondary rows timed after the step loop: unpack,reduce,accumulate,prereduced,perlayer,freegroups,inplace,notinplace,f32class,graph,overlap")
     return ap.parse_args()
 
 
@@ -271,6 +271,31 @@ def add_secondary_buffers(w, phases):
             dst = w._piece("fs3", w.free_s3_total, bf16, off3, b.s3)
             w.free_args.append((l, hzp.ptr_array(owners), dst, owners))
             off1, off3 = off1 + b.s1, off3 + b.s3
+    if "f32class" in phases and getattr(w, "f32_args", None) is None:
+        # the same layers with every tensor of class F32 (fp32 gradients in, fp32 parameters out: 28 + 4R bytes
+        # per parameter), laid out in an arena of its own with the variant the tuner picks
+        cfg = w.cfg
+        tpl = cfg["tensors_per_layer"][:w.n_layers]
+        nt = sum(tpl)
+        w.f32_plan = hzp.hzp_plan(tpl, cfg["tensor_numel"][:nt], cfg["align"], cfg["z3"], cfg["z1"], tensor_class=[1] * nt)
+        w.f32_plan.prepare()
+        A = hzp.HZP_ARENA_ALIGN
+        nbytes = max(w.f32_plan.arena(1, w.R, variant=v) for v in range(hzp.HZP_ARENA_VARIANTS))
+        whole = torch.empty(nbytes + A, dtype=torch.uint8, device=w._dev)
+        off0 = (-whole.data_ptr()) % A
+        variant, secs = w.f32_plan.arena_tune(1, w.rank, w.R, whole.data_ptr() + off0, nbytes)
+        def view(kind, index, layer):
+            off, n = w.f32_plan.arena_slice(1, w.R, kind, index, layer, variant=variant)
+            return whole[off0 + off:off0 + off + n].view(torch.float32)
+        g, p, m, v, o = [], [], [], [], []
+        for l in range(w.n_layers):
+            g += [view(hzp.HZP_STREAM_GRAD, r, l).normal_(0.0, cfg["sigma"]) for r in range(w.R)]
+            p.append(view(hzp.HZP_STREAM_MASTER, 0, l).normal_(0.0, 0.02))
+            m.append(view(hzp.HZP_STREAM_M, 0, l)); v.append(view(hzp.HZP_STREAM_V, 0, l))
+            o.append(view(hzp.HZP_STREAM_PARAM_OUT, 0, l))
+        w.f32_keep = (whole, g, p, m, v, o)
+        w.f32_variant = variant
+        w.f32_args = tuple(hzp.ptr_array(x) for x in (g, p, m, v, o))
     if "reduce" in phases and w.reduce_args is None:
         w.reduce_args = []
         for l, b in enumerate(w.buckets):
@@ -291,6 +316,11 @@ def run_secondary(w, hzp, stream, phase):
         o_arr, l1_src = (w.inplace_o, w.inplace_l1) if phase == "inplace" else (w.o_arr, w.l1_all[0])
         hzp.hzp_adamw_shard(w.plan, 0, w.n_layers, 0, w.rank, hy, w.g_arr, w.R, w.p_arr, w.m_arr, w.v_arr, o_arr, stream=s)
         hzp.hzp_gather_layers(w.plan, 0, w.n_layers, 0, 1, l1_src, w.K, w.l1_all[1], stream=s)
+    elif phase == "f32class":
+        a = w.cfg["adamw"]
+        hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], w.cfg["grad_scale"], 1)
+        g, p, m, v, o = w.f32_args
+        hzp.hzp_adamw_shard(w.f32_plan, 0, w.n_layers, 1, w.rank, hy, g, w.R, p, m, v, o, stream=s)
     elif phase == "perlayer":
         a = w.cfg["adamw"]
         hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], w.cfg["grad_scale"], 1)
@@ -818,17 +848,19 @@ def main():
                       "accumulate": lambda: (4 * R + 8) * w.s3_total,
                       "inplace": lambda: fused_bytes + 4 * w.s1_total * (w.K - 1),
                       "notinplace": lambda: fused_bytes + 4 * w.s1_total * w.K,
+                      "f32class": lambda: (28 + 4 * R) * w.s1_total,
                       "perlayer": lambda: fused_bytes, "freegroups": lambda: 4 * w.free_s3_total,
                       "prereduced": lambda: 30 * w.s1_total}[phase]()
             kname = {"unpack": "unpack_kernel<2>", "reduce": "reduce_kernel<bf16,R=%d>" % R,
                      "accumulate": "reduce_kernel<f32,R=%d,accumulate>" % R,
                      "inplace": "fused update writing into the ZeRO-3 shard + level-1 gather of the other %d pieces" % (w.K - 1),
                      "notinplace": "fused update + level-1 gather of all %d pieces" % w.K,
+                     "f32class": "fused_adamw_kernel<R=%d, fp32 gradients, fp32 output> (class F32 on the same shapes)" % R,
                      "perlayer": "fused_adamw_kernel<R=%d,bf16>, one call per layer" % R,
                      "prereduced": "fused_adamw_kernel<R=1,f32 gradient> (update from a reduced fp32 shard)",
                      "freegroups": "concat_ranges_kernel (Z1=%d over Z3=%d: ZeRO-3 shard from partial owners)"
                                    % (getattr(w, "free_z1", 0), w.z3)}[phase]
-            launches = fused_launches if phase == "prereduced" else 1 if phase in ("inplace", "notinplace") else w.n_layers
+            launches = fused_launches if phase in ("prereduced", "f32class") else 1 if phase in ("inplace", "notinplace") else w.n_layers
             result["secondary"][phase] = roof(kname, nbytes, ms, launches, "%s_%s" % (phase, cfg["name"]))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, torch, np)
