@@ -128,6 +128,27 @@ class Workload:
                 arenas[name] = torch.empty(total, dtype=dtype, device=dev)
             return arenas[name]
 
+        def pack(specs):
+            """Places the stream kinds `specs` = [(name, elements, dtype)] in ONE allocation, each on a 2 MiB
+            boundary an odd number of 2 MiB units after the one before (the default spacing of the planner's
+            arena), instead of one allocation per kind: for the secondary rows' many-stream kernels."""
+            if separate or self.layout != "arena":
+                return
+            A = hzp.HZP_ARENA_ALIGN
+            starts, pos, prev = [], 0, None
+            for name, total, dtype in specs:
+                pos = -(-pos // A) * A
+                if prev is not None and ((pos - prev) // A) % 2 == 0:
+                    pos += A
+                starts.append(pos)
+                prev = pos
+                pos += total * torch.empty(0, dtype=dtype).element_size()
+            whole = torch.empty(pos + A, dtype=torch.uint8, device=dev)
+            off = (-whole.data_ptr()) % A
+            for (name, total, dtype), st in zip(specs, starts):
+                nbytes = total * torch.empty(0, dtype=dtype).element_size()
+                arenas[name] = whole[off + st:off + st + nbytes].view(dtype)
+
         def piece(name, total, dtype, begin, n, fill=None, layer=None):
             """Slice [begin, begin+n) of the arena `name`, or an allocation of its own."""
             st = stream_of(name) if (big is not None and layer is not None) else None
@@ -197,7 +218,7 @@ class Workload:
             self.l3_args.append((l, hzp.ptr_array(shards), bucket.data_ptr()))
         self.l1_all = (hzp.ptr_array(l1_src), hzp.ptr_array(l1_dst))       # the post-step gather of all layers in one call
         self.arenas = arenas
-        self._piece, self._torch, self._hzp, self._dev = piece, torch, hzp, dev
+        self._piece, self._pack, self._torch, self._hzp, self._dev = piece, pack, torch, hzp, dev
         self.unpack_args, self.reduce_args = None, None
         self.l1_per_layer = False
         self.g_arr, self.p_arr = hzp.ptr_array(g_ptrs), hzp.ptr_array(p_ptrs)
@@ -243,6 +264,7 @@ def add_secondary_buffers(w, phases):
     if "accumulate" in phases and getattr(w, "accum_args", None) is None:
         # fp32 contributions accumulated into a resident fp32 gradient shard (one micro-batch)
         w.accum_args = []
+        w._pack([("ag%d" % r, w.s3_total, torch.float32) for r in range(w.R)] + [("acc", w.s3_total, torch.float32)])
         for l, b in enumerate(w.buckets):
             o3 = b.base // w.cfg["z3"]
             slices = [w._piece("ag%d" % r, w.s3_total, torch.float32, o3, b.s3).normal_(0.0, w.cfg["sigma"])
@@ -298,6 +320,7 @@ def add_secondary_buffers(w, phases):
         w.f32_args = tuple(hzp.ptr_array(x) for x in (g, p, m, v, o))
     if "reduce" in phases and w.reduce_args is None:
         w.reduce_args = []
+        w._pack([("rg%d" % r, w.s3_total, bf16) for r in range(w.R)] + [("rout", w.s3_total, torch.float32)])
         for l, b in enumerate(w.buckets):
             o3 = b.base // w.cfg["z3"]
             slices = [w._piece("rg%d" % r, w.s3_total, bf16, o3, b.s3).normal_(0.0, w.cfg["sigma"])
