@@ -529,6 +529,18 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
                     sched.prefetch_tensor(t, needed[t], s)
         sched.join(s)
 
+    def by_parameter_one_call_per_layer():
+        # the same gathers and pool regions, a layer's parameters submitted, acquired and released together
+        for l in range(min(depth, n)):
+            sched.prefetch_params(l, w.l3_args[l][1], s)
+        for l in range(n):
+            sched.acquire_params(l, w.buckets[l].n_tensors, s)
+            compute(l)
+            sched.release_params(l, s)
+            if l + depth < n:
+                sched.prefetch_params(l + depth, w.l3_args[l + depth][1], s)
+        sched.join(s)
+
     t_param = timed(by_parameter)
     sched.drain()
     st = sched.stats()
@@ -537,6 +549,11 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
                             "gather_time_hidden": round((spin["serial_ms"] - t_param) / t_gather, 3),
                             "pool_bytes": st.pool_bytes, "peak_live_bytes": st.peak_live_bytes,
                             "wrap_skipped_bytes_per_pass": st.wrap_skipped_bytes // (rounds + 1)}
+    t_layer = timed(by_parameter_one_call_per_layer)
+    sched.drain()
+    out["per_parameter_one_call_per_layer"] = {
+        "compute": "spin", "gathers_per_pass": first[-1], "scheduled_ms": round(t_layer, 3),
+        "gather_time_hidden": round((spin["serial_ms"] - t_layer) / t_gather, 3)}
     sched.destroy()
     return out
 

@@ -508,6 +508,23 @@ hzp_status_t hzp_sched_prefetch_tensor(hzp_sched_t *sched, uint32_t tensor_id, c
                                        uint32_t n_shards, hipStream_t producer);
 hzp_status_t hzp_sched_acquire_tensor(hzp_sched_t *sched, uint32_t tensor_id, hipStream_t consumer, void **tensor);
 hzp_status_t hzp_sched_release_tensor(hzp_sched_t *sched, uint32_t tensor_id, hipStream_t consumer);
+
+/* The parameters of one layer at parameter granularity with one call each: hzp_sched_prefetch_params
+ * submits one gather and takes one pool region per tensor of bucket (layer, cls), in tensor order,
+ * all or nothing (NOMEM, nothing submitted, if the pool or the slot count cannot take them all;
+ * with several threads submitting at once a later tensor can still meet NOMEM, and the earlier
+ * ones stay prefetched); the producer's stream is marked once.  hzp_sched_acquire_params makes
+ * `consumer` wait for all of them with one stream operation (the gathers run in order on the
+ * scheduler's gather stream) and returns the tensors' addresses in bucket order (`tensors`: HOST
+ * array of n_tensors of the bucket).  hzp_sched_release_params gives the regions back behind one
+ * event on `consumer` (two where the ring wrapped inside the layer).  They work on the same regions
+ * as the _tensor calls and may be mixed with them.
+ *   shard_ptrs : HOST array [Z3] of device pointers to the layer's ZeRO-3 shards, all non-NULL
+ * Errors: as hzp_sched_prefetch_tensor / _acquire_tensor / _release_tensor. */
+hzp_status_t hzp_sched_prefetch_params(hzp_sched_t *sched, uint32_t layer, const void *const *shard_ptrs,
+                                       uint32_t n_shards, hipStream_t producer);
+hzp_status_t hzp_sched_acquire_params(hzp_sched_t *sched, uint32_t layer, hipStream_t consumer, void **tensors);
+hzp_status_t hzp_sched_release_params(hzp_sched_t *sched, uint32_t layer, hipStream_t consumer);
 /* Queue hzp_reduce_shard(layer, level, rank, ...) on the reduction stream, to run after the work
  * already enqueued on `producer` (which wrote the gradients).  Arguments are checked now, as by
  * hzp_reduce_shard; the pointer array is copied.  Returns at once. */

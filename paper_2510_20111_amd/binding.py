@@ -31,7 +31,8 @@ EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_prepare", "hzp_plan_info", "hz
            "hzp_memory_model", "hzp_choose_groups",
            "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_prefetch_ahead", "hzp_sched_acquire",
            "hzp_sched_release", "hzp_sched_prefetch_tensor", "hzp_sched_acquire_tensor",
-           "hzp_sched_release_tensor", "hzp_sched_reduce", "hzp_sched_join", "hzp_sched_drain", "hzp_sched_stats"]
+           "hzp_sched_release_tensor", "hzp_sched_prefetch_params", "hzp_sched_acquire_params",
+           "hzp_sched_release_params", "hzp_sched_reduce", "hzp_sched_join", "hzp_sched_drain", "hzp_sched_stats"]
 
 
 class HzpError(RuntimeError):
@@ -169,6 +170,12 @@ def _load():
     L.hzp_sched_acquire_tensor.argtypes = [vp, u32, vp, ctypes.POINTER(vp)]
     L.hzp_sched_release_tensor.restype = ctypes.c_int
     L.hzp_sched_release_tensor.argtypes = [vp, u32, vp]
+    L.hzp_sched_prefetch_params.restype = ctypes.c_int
+    L.hzp_sched_prefetch_params.argtypes = [vp, u32, vp, u32, vp]
+    L.hzp_sched_acquire_params.restype = ctypes.c_int
+    L.hzp_sched_acquire_params.argtypes = [vp, u32, vp, ctypes.POINTER(ctypes.c_void_p)]
+    L.hzp_sched_release_params.restype = ctypes.c_int
+    L.hzp_sched_release_params.argtypes = [vp, u32, vp]
     L.hzp_sched_reduce.restype = ctypes.c_int
     L.hzp_sched_reduce.argtypes = [vp, u32, ctypes.c_int, u32, vp, u32, u32, ctypes.c_float, ctypes.c_int, vp, vp]
     L.hzp_sched_join.restype = ctypes.c_int
@@ -431,6 +438,19 @@ class Sched:
 
     def release_tensor(self, tensor_id, consumer=None):
         _check(_L.hzp_sched_release_tensor(self.handle, tensor_id, _stream(consumer)))
+
+    def prefetch_params(self, layer, shard_ptrs, producer=None):
+        arr = ptr_array(shard_ptrs)
+        _check(_L.hzp_sched_prefetch_params(self.handle, layer, arr, len(arr), _stream(producer)))
+
+    def acquire_params(self, layer, n_tensors, consumer=None):
+        """Device addresses of the layer's tensors in the pool, in bucket order."""
+        out = (ctypes.c_void_p * n_tensors)()
+        _check(_L.hzp_sched_acquire_params(self.handle, layer, _stream(consumer), out))
+        return [int(x or 0) for x in out]
+
+    def release_params(self, layer, consumer=None):
+        _check(_L.hzp_sched_release_params(self.handle, layer, _stream(consumer)))
 
     def reduce(self, layer, level, rank, grad_slices, scale, accumulate, out_f32, producer=None,
                grad_dtype=HZP_GRAD_DEFAULT):

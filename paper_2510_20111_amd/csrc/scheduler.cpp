@@ -133,33 +133,42 @@ hipError_t take_event(hzp_sched *s, hipEvent_t *ev)
     return hipEventCreateWithFlags(ev, hipEventDisableTiming);
 }
 
+// The live run of the ring: [tail, head) if head > tail, else [tail, cap) and [0, head).
+struct RingSpan {
+    bool empty;
+    uint64_t tail, head;
+};
+
+RingSpan ring_span(const hzp_sched *s)
+{
+    if (s->live.empty()) return RingSpan{true, 0, 0};
+    return RingSpan{false, s->live.front().off, s->live.back().off + s->live.back().bytes};
+}
+
 // Next region of the ring for `bytes`, or false if the live data leaves no room.  `skipped` is the
 // space lost at the end of the buffer when the region has to start over at offset 0.
-bool ring_take(const hzp_sched *s, uint64_t bytes, uint64_t *off, uint64_t *skipped)
+bool ring_take(uint64_t cap, const RingSpan &r, uint64_t bytes, uint64_t *off, uint64_t *skipped)
 {
-    const uint64_t cap = s->pool_bytes;
     *skipped = 0;
     if (bytes > cap) return false;
-    if (s->live.empty()) {
+    if (r.empty) {
         *off = 0;
         return true;
     }
-    const uint64_t tail = s->live.front().off;
-    const uint64_t head = s->live.back().off + s->live.back().bytes;
-    if (head > tail) {                      // live data is the single run [tail, head)
-        if (head + bytes <= cap) {
-            *off = head;
+    if (r.head > r.tail) {                  // live data is the single run [tail, head)
+        if (r.head + bytes <= cap) {
+            *off = r.head;
             return true;
         }
-        if (bytes <= tail) {                // start over; [head, cap) stays unused this time round
+        if (bytes <= r.tail) {              // start over; [head, cap) stays unused this time round
             *off = 0;
-            *skipped = cap - head;
+            *skipped = cap - r.head;
             return true;
         }
         return false;
     }
-    if (head + bytes <= tail) {             // live data wraps: [tail, cap) and [0, head)
-        *off = head;
+    if (r.head + bytes <= r.tail) {         // live data wraps: [tail, cap) and [0, head)
+        *off = r.head;
         return true;
     }
     return false;
@@ -180,7 +189,8 @@ void worker_main(hzp_sched *s)
         if (cmd.kind == Cmd::STOP) break;
         if (cmd.kind == Cmd::PREFETCH) {
             // The shards exist once the producer's work enqueued before the prefetch has run.
-            hipError_t e = hipStreamWaitEvent(s->gather_stream, cmd.after, 0);
+            // (a command that follows another of the same submission carries no event of its own)
+            hipError_t e = cmd.after ? hipStreamWaitEvent(s->gather_stream, cmd.after, 0) : hipSuccess;
             for (hipEvent_t ev : cmd.wait)          // earlier users of this part of the ring
                 if (e == hipSuccess) e = hipStreamWaitEvent(s->gather_stream, ev, 0);
             hzp_status_t st = HZP_OK;
@@ -196,7 +206,7 @@ void worker_main(hzp_sched *s)
             }
             if (e == hipSuccess && st == HZP_OK) e = hipEventRecord(cmd.ready, s->gather_stream);
             std::lock_guard<std::mutex> lock(s->mu);
-            s->spare_events.push_back(cmd.after);
+            if (cmd.after) s->spare_events.push_back(cmd.after);
             for (hipEvent_t ev : cmd.wait) s->spare_events.push_back(ev);   // their waits are enqueued: reusable
             if (e != hipSuccess || st != HZP_OK) {
                 s->set_failed(st != HZP_OK ? st : HZP_ERR_HIP, st != HZP_OK ? hzp_last_error() : hipGetErrorString(e));
@@ -262,18 +272,20 @@ void sweep_freed(hzp_sched *s)
     s->freed.resize(kept);
 }
 
-// Common part of the two prefetch calls; `ptrs` have been validated.
-hzp_status_t prefetch_region(hzp_sched *s, const char *who, uint64_t key, bool is_tensor, uint32_t id, uint64_t payload,
-                             const void *const *ptrs, uint32_t n, hipStream_t producer)
+// Common part of the prefetch calls; `ptrs` have been validated and the caller holds the lock.
+// `mark_producer`: record an event on the producer's stream for the gather to wait for (the later
+// commands of one submission are ordered behind the first on the gather stream and need none).
+hzp_status_t prefetch_region(hzp_sched *s, std::unique_lock<std::mutex> &lock, const char *who, uint64_t key,
+                             bool is_tensor, uint32_t id, uint64_t payload, const void *const *ptrs, uint32_t n,
+                             hipStream_t producer, bool mark_producer)
 {
-    std::unique_lock<std::mutex> lock(s->mu);
     if (s->failed != HZP_OK) return fail(s->failed, "scheduler failed earlier: %s", s->fail_text);
     if (s->find(key)) return fail(HZP_ERR_INVALID_ARG, "%s %u is already in the pool", who, id);
     if (s->live.size() >= s->max_live)
         return fail(HZP_ERR_NOMEM, "%s %u: %u regions are between prefetch and release already", who, id, s->max_live);
     const uint64_t bytes = s->uniform_bytes ? s->uniform_bytes : (payload + 255) / 256 * 256;
     uint64_t off = 0, skipped = 0;
-    if (!ring_take(s, bytes, &off, &skipped))
+    if (!ring_take(s->pool_bytes, ring_span(s), bytes, &off, &skipped))
         return fail(HZP_ERR_NOMEM, "%s %u: the pool has no room for %llu bytes until older regions are released; "
                                    "release in the order of the prefetches", who, id, (unsigned long long)bytes);
     Cmd cmd;
@@ -285,14 +297,17 @@ hzp_status_t prefetch_region(hzp_sched *s, const char *who, uint64_t key, bool i
     cmd.ptrs.assign(ptrs, ptrs + n);
     hipError_t e = take_event(s, &cmd.ready);
     if (e != hipSuccess) return hip_fail(s, who, e);
-    e = take_event(s, &cmd.after);
-    if (e == hipSuccess) {
-        e = hipEventRecord(cmd.after, producer);
-        if (e != hipSuccess) s->spare_events.push_back(cmd.after);
-    }
-    if (e != hipSuccess) {
-        s->spare_events.push_back(cmd.ready);
-        return hip_fail(s, who, e);
+    if (mark_producer) {
+        e = take_event(s, &cmd.after);
+        if (e == hipSuccess) {
+            e = hipEventRecord(cmd.after, producer);
+            if (e != hipSuccess) s->spare_events.push_back(cmd.after);
+        }
+        if (e != hipSuccess) {
+            s->spare_events.push_back(cmd.ready);
+            cmd.after = nullptr;
+            return hip_fail(s, who, e);
+        }
     }
     const hipEvent_t after = cmd.after;
     // The gather must run after the last use of everything that lay in [off, off+bytes) before.
@@ -320,7 +335,7 @@ hzp_status_t prefetch_region(hzp_sched *s, const char *who, uint64_t key, bool i
     if (st != HZP_OK) {             // not queued: undo
         s->live.pop_back();
         s->spare_events.push_back(a.ready);
-        s->spare_events.push_back(after);
+        if (after) s->spare_events.push_back(after);
         s->freed.insert(s->freed.end(), taken.begin(), taken.end());
         return st;
     }
@@ -484,8 +499,9 @@ extern "C" hzp_status_t hzp_sched_prefetch(hzp_sched_t *s, uint32_t layer, const
         if (reinterpret_cast<uintptr_t>(shard_ptrs[i]) & 15u)
             return fail(HZP_ERR_ALIGN, "hzp_sched_prefetch: shard %u is not 16-byte aligned", i);
     }
-    return prefetch_region(s, "hzp_sched_prefetch: layer", layer, false, layer,
-                           b->P * (s->cls == HZP_CLASS_F32 ? 4 : 2), shard_ptrs, n_shards, producer);
+    std::unique_lock<std::mutex> lock(s->mu);
+    return prefetch_region(s, lock, "hzp_sched_prefetch: layer", layer, false, layer,
+                           b->P * (s->cls == HZP_CLASS_F32 ? 4 : 2), shard_ptrs, n_shards, producer, true);
 }
 
 extern "C" hzp_status_t hzp_sched_prefetch_ahead(hzp_sched_t *s, uint32_t first_layer, uint32_t n_layers,
@@ -532,8 +548,164 @@ extern "C" hzp_status_t hzp_sched_prefetch_tensor(hzp_sched_t *s, uint32_t tenso
             return fail(HZP_ERR_ALIGN, "hzp_sched_prefetch_tensor: shard %llu is not 16-byte aligned",
                         (unsigned long long)j);
     }
-    return prefetch_region(s, "hzp_sched_prefetch_tensor: tensor", kTensorKey | tensor_id, true, tensor_id,
-                           t.numel * (s->cls == HZP_CLASS_F32 ? 4 : 2), shard_ptrs, n_shards, producer);
+    std::unique_lock<std::mutex> lock(s->mu);
+    return prefetch_region(s, lock, "hzp_sched_prefetch_tensor: tensor", kTensorKey | tensor_id, true, tensor_id,
+                           t.numel * (s->cls == HZP_CLASS_F32 ? 4 : 2), shard_ptrs, n_shards, producer, true);
+}
+
+// The parameters of one layer at the granularity Section 4.2 prefers -- one gather and one region of
+// the pool per parameter -- submitted, acquired and released with one call each, so that the host
+// calls and the stream operations on the consumer's stream do not grow with the number of parameters.
+extern "C" hzp_status_t hzp_sched_prefetch_params(hzp_sched_t *s, uint32_t layer, const void *const *shard_ptrs,
+                                                  uint32_t n_shards, hipStream_t producer)
+{
+    if (!s || !shard_ptrs) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_prefetch_params: NULL argument");
+    const BucketRec *b = find_bucket(s->plan, layer, s->cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_sched_prefetch_params: no bucket (layer %u, class %u)", layer, s->cls);
+    if (n_shards != s->plan->z3)
+        return fail(HZP_ERR_INVALID_ARG, "hzp_sched_prefetch_params: takes %u shards, got %u", s->plan->z3, n_shards);
+    if (n_shards > HZP_MAX_GROUP)
+        return fail(HZP_ERR_UNSUPPORTED, "hzp_sched_prefetch_params: %u shards exceed %u", n_shards, HZP_MAX_GROUP);
+    for (uint32_t i = 0; i < n_shards; ++i) {
+        if (!shard_ptrs[i]) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_prefetch_params: shard %u is NULL", i);
+        if (reinterpret_cast<uintptr_t>(shard_ptrs[i]) & 15u)
+            return fail(HZP_ERR_ALIGN, "hzp_sched_prefetch_params: shard %u is not 16-byte aligned", i);
+    }
+    const uint64_t es = s->cls == HZP_CLASS_F32 ? 4 : 2;
+    std::unique_lock<std::mutex> lock(s->mu);
+    if (s->failed != HZP_OK) return fail(s->failed, "scheduler failed earlier: %s", s->fail_text);
+    for (uint32_t tid : b->tensor_ids)
+        if (s->find(kTensorKey | tid))
+            return fail(HZP_ERR_INVALID_ARG, "hzp_sched_prefetch_params: tensor %u is already in the pool", tid);
+    // All or nothing: walk the ring for every parameter first.
+    if (s->live.size() + b->tensor_ids.size() > s->max_live)
+        return fail(HZP_ERR_NOMEM, "hzp_sched_prefetch_params: layer %u: %zu more regions do not fit beside the %zu "
+                                   "between prefetch and release (at most %u)", layer, b->tensor_ids.size(), s->live.size(),
+                    s->max_live);
+    RingSpan span = ring_span(s);
+    for (uint32_t tid : b->tensor_ids) {
+        const uint64_t payload = s->plan->tensors[tid].numel * es;
+        const uint64_t bytes = s->uniform_bytes ? s->uniform_bytes : (payload + 255) / 256 * 256;
+        uint64_t off = 0, skipped = 0;
+        if (!ring_take(s->pool_bytes, span, bytes, &off, &skipped))
+            return fail(HZP_ERR_NOMEM, "hzp_sched_prefetch_params: layer %u: the pool has no room for all of its "
+                                       "parameters until older regions are released", layer);
+        if (span.empty) span = RingSpan{false, off, off + bytes};
+        else span.head = off + bytes;
+    }
+    bool first = true;
+    for (uint32_t tid : b->tensor_ids) {
+        const hzp_status_t st = prefetch_region(s, lock, "hzp_sched_prefetch_params: tensor", kTensorKey | tid, true, tid,
+                                                s->plan->tensors[tid].numel * es, shard_ptrs, n_shards, producer, first);
+        if (st != HZP_OK) return st;        // the queue stayed full or a HIP call failed: the scheduler is failed
+        first = false;
+    }
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_sched_acquire_params(hzp_sched_t *s, uint32_t layer, hipStream_t consumer, void **tensors)
+{
+    if (!s || !tensors) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_acquire_params: NULL argument");
+    const BucketRec *b = find_bucket(s->plan, layer, s->cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_sched_acquire_params: no bucket (layer %u, class %u)", layer, s->cls);
+    std::unique_lock<std::mutex> lock(s->mu);
+    for (uint32_t tid : b->tensor_ids) {
+        const Alloc *a = s->find(kTensorKey | tid);
+        if (!a) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_acquire_params: tensor %u was not prefetched", tid);
+        if (a->state == A_ACQUIRED)
+            return fail(HZP_ERR_INVALID_ARG, "hzp_sched_acquire_params: tensor %u is already acquired", tid);
+    }
+    // Host-side wait until the background thread has launched every gather of the layer (not until
+    // they have run).  They are launched in order, so the last one's state tells.
+    const uint64_t last_key = kTensorKey | b->tensor_ids.back();
+    const auto t0 = std::chrono::steady_clock::now();
+    const bool ok = s->cv.wait_for(lock, kHostWaitLimit, [&] {
+        const Alloc *x = s->find(last_key);
+        return s->failed != HZP_OK || (x && x->state == A_READY);
+    });
+    s->stats.acquire_host_wait_us += (uint64_t)std::chrono::duration_cast<std::chrono::microseconds>(
+                                         std::chrono::steady_clock::now() - t0).count();
+    if (s->failed != HZP_OK) return fail(s->failed, "scheduler failed earlier: %s", s->fail_text);
+    if (!ok) {
+        s->set_failed(HZP_ERR_HIP, "scheduler: a prefetch was not issued within the time limit");
+        return fail(HZP_ERR_HIP, "%s", s->fail_text);
+    }
+    // One wait on the consumer's stream: the gathers run in order on the one gather stream, so the
+    // last one's event covers them all -- unless some were prefetched one by one in another order,
+    // in which case every event is waited for.
+    bool in_order = true;
+    {
+        size_t next = 0;                        // entries of the deque lie in prefetch order
+        for (const Alloc &x : s->live) {
+            if (x.state == A_RELEASED || !(x.key & kTensorKey)) continue;
+            const uint32_t tid = (uint32_t)(x.key & 0xFFFFFFFFull);
+            if (next < b->tensor_ids.size() && tid == b->tensor_ids[next]) {
+                ++next;
+            } else if (s->plan->tensors[tid].bucket == (uint32_t)(b - s->plan->buckets.data()) && next < b->tensor_ids.size()) {
+                in_order = false;               // one of this layer's, but not the next one
+            }
+        }
+        if (next != b->tensor_ids.size()) in_order = false;
+    }
+    for (size_t i = 0; i < b->tensor_ids.size(); ++i) {
+        Alloc *a = s->find(kTensorKey | b->tensor_ids[i]);
+        if (!in_order || i + 1 == b->tensor_ids.size()) {
+            const hipError_t e = hipStreamWaitEvent(consumer, a->ready, 0);
+            if (e != hipSuccess) return hip_fail(s, "hzp_sched_acquire_params", e);
+        }
+    }
+    for (size_t i = 0; i < b->tensor_ids.size(); ++i) {
+        Alloc *a = s->find(kTensorKey | b->tensor_ids[i]);
+        a->state = A_ACQUIRED;
+        tensors[i] = s->pool + a->off;
+    }
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_sched_release_params(hzp_sched_t *s, uint32_t layer, hipStream_t consumer)
+{
+    if (!s) return fail(HZP_ERR_INVALID_ARG, "hzp_sched_release_params: NULL scheduler");
+    const BucketRec *b = find_bucket(s->plan, layer, s->cls);
+    if (!b) return fail(HZP_ERR_RANGE, "hzp_sched_release_params: no bucket (layer %u, class %u)", layer, s->cls);
+    std::unique_lock<std::mutex> lock(s->mu);
+    for (uint32_t tid : b->tensor_ids) {
+        const Alloc *a = s->find(kTensorKey | tid);
+        if (!a || a->state != A_ACQUIRED)
+            return fail(HZP_ERR_INVALID_ARG, "hzp_sched_release_params: tensor %u is not acquired", tid);
+    }
+    // Regions that lie back to back in the pool are given back as one, behind one event on the
+    // consumer's stream (a layer's parameters form one run, two where the ring wrapped).
+    if (s->freed.size() >= kFreedSweep) sweep_freed(s);
+    uint64_t run_off = 0, run_bytes = 0;
+    auto give_back = [&]() -> hipError_t {
+        if (run_bytes == 0) return hipSuccess;
+        hipEvent_t ev = nullptr;
+        hipError_t e = take_event(s, &ev);
+        if (e == hipSuccess) {
+            e = hipEventRecord(ev, consumer);
+            if (e != hipSuccess) s->spare_events.push_back(ev);
+        }
+        if (e == hipSuccess) s->freed.push_back(FreedRegion{run_off, run_bytes, ev});
+        run_bytes = 0;
+        return e;
+    };
+    for (uint32_t tid : b->tensor_ids) {
+        Alloc *a = s->find(kTensorKey | tid);
+        if (run_bytes != 0 && a->off != run_off + run_bytes) {
+            const hipError_t e = give_back();
+            if (e != hipSuccess) return hip_fail(s, "hzp_sched_release_params", e);
+        }
+        if (run_bytes == 0) run_off = a->off;
+        run_bytes += a->bytes;
+        s->spare_events.push_back(a->ready);    // the consumer's wait on it (or on a later one) was enqueued at acquire
+        a->ready = nullptr;
+        a->state = A_RELEASED;
+    }
+    const hipError_t e = give_back();
+    if (e != hipSuccess) return hip_fail(s, "hzp_sched_release_params", e);
+    while (!s->live.empty() && s->live.front().state == A_RELEASED) s->live.pop_front();
+    s->cv.notify_all();
+    return HZP_OK;
 }
 
 extern "C" hzp_status_t hzp_sched_acquire(hzp_sched_t *s, uint32_t layer, hipStream_t consumer, void **bucket)

@@ -246,6 +246,17 @@ def test_scheduler_argument_errors_before_any_gpu_call():
     with pytest.raises(hzp.HzpError) as e:
         hzp.Sched(only_bf16, cls=hzp.HZP_CLASS_F32)
     assert e.value.status == hzp.HZP_ERR_RANGE
+    # every scheduler call refuses a NULL scheduler before touching anything
+    import ctypes
+    L = ctypes.CDLL(hzp.LIB_PATH)
+    for name, args in [("hzp_sched_prefetch_params", (None, 0, None, 0, None)),
+                       ("hzp_sched_acquire_params", (None, 0, None, None)),
+                       ("hzp_sched_release_params", (None, 0, None)),
+                       ("hzp_sched_release_tensor", (None, 0, None)),
+                       ("hzp_sched_join", (None, None)), ("hzp_sched_drain", (None,))]:
+        fn = getattr(L, name)
+        fn.restype = ctypes.c_int
+        assert fn(*args) == hzp.HZP_ERR_INVALID_ARG, name
 
 
 def test_shards_of_2_to_the_30_elements_are_refused_before_any_launch():

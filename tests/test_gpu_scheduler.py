@@ -407,3 +407,65 @@ def test_prefetch_one_parameter_at_a_time():
     st = sched.stats()
     assert st.gathers_issued == n_t and st.peak_live_slots == 3
     sched.destroy()
+
+
+def test_a_layers_parameters_with_one_call_each():
+    """Parameter granularity (one gather and one pool region per tensor) driven with one prefetch, one
+    acquire and one release per layer, two layers ahead, through a ring that wraps inside layers; mixed
+    with the one-tensor calls on one layer; all-or-nothing back-pressure."""
+    say("scheduler: a layer's parameters with one call each")
+    desc = hzp_inputs.irregular_desc(42, seed=71, max_numel=60000, tensors_per_layer=6, f32_every=0)
+    desc = dict(desc, tensor_class=None, tensor_wd_mult=None)
+    z3 = 4
+    oplan, plan = oracle_plan(desc, 8, z3, 8), lib_plan(desc, 8, z3, 8)
+    rng = np.random.default_rng(72)
+    shards, dshards = {}, {}
+    for bi, b in enumerate(oplan["buckets"]):
+        bucket = rng.integers(0, 1 << 16, size=b["P"], dtype=np.uint64).astype(np.uint16)
+        shards[bi] = [np.ascontiguousarray(bucket[j * b["S3"]:(j + 1) * b["S3"]]) for j in range(z3)]
+        dshards[bi] = [to_dev(s) for s in shards[bi]]
+    n_layers = oplan["n_layers"]
+    ids = [op.find_bucket(oplan, l, 0)["tensor_ids"] for l in range(n_layers)]
+    layer_bytes = [sum((2 * oplan["tensors"][t]["numel"] + 255) // 256 * 256 for t in ids[l]) for l in range(n_layers)]
+    # room for two and a half of the largest layers: the ring wraps in the middle of layers
+    pool = (5 * max(layer_bytes) // 2 + 255) // 256 * 256
+    sched = hzp.Sched(plan, gather_slots=12, queue_capacity=16, pool_bytes=pool)
+    consumer = torch.cuda.Stream()
+    outs = [torch.zeros(t["numel"], dtype=torch.int16, device=DEV) for t in oplan["tensors"]]
+    torch.cuda.synchronize()
+    sched.prefetch_params(0, dshards[0])
+    sched.prefetch_params(1, dshards[1])
+    with pytest.raises(hzp.HzpError) as e:
+        sched.prefetch_params(2, dshards[2])                        # 12 regions are live: nothing of layer 2 is taken
+    assert e.value.status == hzp.HZP_ERR_NOMEM
+    assert sched.stats().peak_live_slots == 12
+    with pytest.raises(hzp.HzpError) as e:
+        sched.prefetch_params(1, dshards[1])                        # already in the pool
+    assert e.value.status == hzp.HZP_ERR_INVALID_ARG
+    with pytest.raises(hzp.HzpError) as e:
+        sched.release_params(0, consumer)                           # not acquired yet
+    assert e.value.status == hzp.HZP_ERR_INVALID_ARG
+    for l in range(n_layers):
+        if l == 3:                                                  # this layer one tensor at a time
+            ptrs = [sched.acquire_tensor(t, consumer) for t in ids[l]]
+        else:
+            ptrs = sched.acquire_params(l, len(ids[l]), consumer)
+        with torch.cuda.stream(consumer):
+            for t, ptr in zip(ids[l], ptrs):
+                outs[t].copy_(view16(ptr, outs[t].numel()))
+        if l == 4:
+            for t in ids[l]:
+                sched.release_tensor(t, consumer)
+        else:
+            sched.release_params(l, consumer)
+        if l + 2 < n_layers:
+            sched.prefetch_params(l + 2, dshards[l + 2])
+    consumer.synchronize()
+    sched.drain()
+    for t, rec in enumerate(oplan["tensors"]):
+        want = on.unpack_tensor(shards[rec["bucket"]], rec["offset"], rec["numel"])
+        assert np.array_equal(to_host(outs[t], np.uint16), want), t
+    st = sched.stats()
+    assert st.gathers_issued == len(oplan["tensors"]) and st.peak_live_slots == 12
+    assert st.wrap_skipped_bytes > 0                                # the ring did wrap
+    sched.destroy()
