@@ -744,31 +744,34 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
     fused_bytes = (26 + 2 * R) * w.s1_total
     g1_bytes, g3_bytes = 4 * w.s3_total, 4 * w.p_total
 
-    def roof(kernel, algo_bytes, ms, launches, key):
+    def roof(kernel, algo_bytes, ms, launches, key, per_step=None):
         per_launch_ms = ms / launches
         ach = algo_bytes / launches / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
         return {"kernel": kernel, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": read_traffic(key),
                 "traffic_key": key, "launches_per_step": launches, "avg_launch_us": round(per_launch_ms * 1e3, 2),
                 "algorithmic_bytes_per_launch": algo_bytes / launches,
-                "share_of_step_time": round(ms / max(fused_ms + g1_ms + g3_ms, 1e-9), 3)}
+                "share_of_step_time": round(ms / max(fused_ms + g1_ms + g3_ms, 1e-9), 3),
+                # over the timed steps (each step's launches of the kernel bracketed by one event pair)
+                "median_launch_us": None if per_step is None else round(float(np.median(per_step)) / launches * 1e3, 2),
+                "min_launch_us": None if per_step is None else round(float(per_step.min()) / launches * 1e3, 2)}
 
     fused_launches = fused_launch_count(w)
     rooflines = {}
     if "fused" in phases:
         rooflines["fused_adamw"] = roof("fused_adamw_kernel<R=%d,bf16>" % R, fused_bytes, fused_ms,
-                                        fused_launches, "fused_adamw_%s" % cfg["name"])
+                                        fused_launches, "fused_adamw_%s" % cfg["name"], ph[:, 0])
     if "gather1" in phases:
         if w.l1_per_layer:
             rooflines["gather_level1"] = roof("concat_kernel (K=%d x S1 -> S3)" % w.K, g1_bytes, g1_ms,
-                                              w.n_layers, "concat_l1_%s" % cfg["name"])
+                                              w.n_layers, "concat_l1_%s" % cfg["name"], ph[:, 1])
         else:
             pieces = w.n_layers * w.K               # one launch of the layer-range gather holds 192 pieces
             rooflines["gather_level1"] = roof("concat_layers_kernel (all layers, K=%d x S1 -> S3)" % w.K, g1_bytes,
-                                              g1_ms, -(-pieces // 192), "concat_layers_l1_%s" % cfg["name"])
+                                              g1_ms, -(-pieces // 192), "concat_layers_l1_%s" % cfg["name"], ph[:, 1])
     if "gather3" in phases:
         rooflines["gather_level3"] = roof("concat_kernel (Z3=%d x S3 -> P)" % w.z3, g3_bytes, g3_ms,
-                                          w.n_layers, "concat_l3_%s" % cfg["name"])
+                                          w.n_layers, "concat_l3_%s" % cfg["name"], ph[:, 2])
     out = {
         "cfg": cfg, "w": w if keep else None, "stream": stream if keep else None, "rank": rank, "phases": phases,
         "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "rooflines": rooflines,
@@ -800,7 +803,7 @@ def workload_text(t):
 def triple(t):
     """The {fused, gather1, gather3} rooflines of a timed workload, for the per-workload map."""
     r = t["rooflines"]
-    short = lambda x: None if x is None else {k: x[k] for k in ("kernel", "achieved", "frac", "avg_launch_us",
+    short = lambda x: None if x is None else {k: x[k] for k in ("kernel", "achieved", "frac", "avg_launch_us", "median_launch_us", "min_launch_us",
                                                                "launches_per_step", "algorithmic_bytes_per_launch",
                                                                "traffic", "traffic_key")}
     return {"workload": workload_text(t), "steps": t["steps"], "ms_per_step": round(t["ms_per_step"], 4),
@@ -861,7 +864,7 @@ def main():
     }
     fused_bytes, fused_launches = t["fused_bytes"], t["fused_launches"]
 
-    def roof(kernel, algo_bytes, ms, launches, key):
+    def roof(kernel, algo_bytes, ms, launches, key, per_step=None):
         per_launch_ms = ms / launches
         ach = algo_bytes / launches / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
         return {"kernel": kernel, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
