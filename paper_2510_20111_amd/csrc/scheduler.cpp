@@ -616,12 +616,15 @@ extern "C" hzp_status_t hzp_sched_acquire_params(hzp_sched_t *s, uint32_t layer,
             return fail(HZP_ERR_INVALID_ARG, "hzp_sched_acquire_params: tensor %u is already acquired", tid);
     }
     // Host-side wait until the background thread has launched every gather of the layer (not until
-    // they have run).  They are launched in order, so the last one's state tells.
-    const uint64_t last_key = kTensorKey | b->tensor_ids.back();
+    // they have run): an event that has not been recorded yet cannot be waited for.
     const auto t0 = std::chrono::steady_clock::now();
     const bool ok = s->cv.wait_for(lock, kHostWaitLimit, [&] {
-        const Alloc *x = s->find(last_key);
-        return s->failed != HZP_OK || (x && x->state == A_READY);
+        if (s->failed != HZP_OK) return true;
+        for (uint32_t tid : b->tensor_ids) {
+            const Alloc *x = s->find(kTensorKey | tid);
+            if (!x || x->state != A_READY) return false;
+        }
+        return true;
     });
     s->stats.acquire_host_wait_us += (uint64_t)std::chrono::duration_cast<std::chrono::microseconds>(
                                          std::chrono::steady_clock::now() - t0).count();

@@ -458,7 +458,10 @@ def test_a_layers_parameters_with_one_call_each():
                 sched.release_tensor(t, consumer)
         else:
             sched.release_params(l, consumer)
-        if l + 2 < n_layers:
+        if l + 2 == 5:                                              # one by one and backwards: acquired together all the same
+            for t in reversed(ids[5]):
+                sched.prefetch_tensor(t, dshards[5])
+        elif l + 2 < n_layers:
             sched.prefetch_params(l + 2, dshards[l + 2])
     consumer.synchronize()
     sched.drain()
