@@ -110,6 +110,7 @@ int main()
 
     std::vector<uint16_t> hg[2][4], hout[2], hshard3[2];
     std::vector<float> hp[2], hm[2], hv[2];
+    std::vector<float> hp0[2], hm0[2], hv0[2];      // the inputs as they were (the oracle updates hp, hm, hv in place)
     const void *dgrad[8];
     float *dp[2], *dm[2], *dv[2];
     void *dout[2];
@@ -140,6 +141,9 @@ int main()
             dgrad[l * R + r] = to_device(hg[l][r]);
             if (!dgrad[l * R + r]) return 2;
         }
+        hp0[l] = hp[l];
+        hm0[l] = hm[l];
+        hv0[l] = hv[l];
         dp[l] = to_device(hp[l]);
         dm[l] = to_device(hm[l]);
         dv[l] = to_device(hv[l]);
@@ -257,11 +261,73 @@ int main()
         }
     }
 
+    // the arena layout, the tuner's choice of a variant, and the update on slices carved from the arena
+    {
+        uint64_t total[HZP_ARENA_VARIANTS], largest = 0;
+        for (uint32_t v = 0; v < HZP_ARENA_VARIANTS; ++v) {
+            HZP(hzp_plan_arena(plan, HZP_CLASS_BF16, R, HZP_GRAD_DEFAULT, v, &total[v]));
+            if (total[v] > largest) largest = total[v];
+        }
+        char *raw = nullptr;
+        HIP(hipMalloc((void **)&raw, largest + HZP_ARENA_ALIGN));
+        char *arena = raw + (HZP_ARENA_ALIGN - (uintptr_t)raw % HZP_ARENA_ALIGN) % HZP_ARENA_ALIGN;
+        uint32_t variant = 99;
+        double seconds[HZP_ARENA_VARIANTS];
+        HZP(hzp_arena_tune(plan, HZP_CLASS_BF16, rank, R, arena, largest, stream, &variant, seconds));
+        if (variant >= HZP_ARENA_VARIANTS || !(seconds[variant] > 0.0)) {
+            bad++;
+            printf("selftest: the tuner chose variant %u\n", variant);
+            variant = 0;
+        }
+        std::vector<unsigned char> zeros(largest, 1);
+        HIP(hipMemcpy(zeros.data(), arena, largest, hipMemcpyDeviceToHost));
+        for (uint64_t x = 0; x < largest; ++x)
+            if (zeros[x]) {
+                bad++;
+                printf("selftest: the arena is not clear after tuning (byte %llu)\n", (unsigned long long)x);
+                break;
+            }
+        // the same update as above, this time from the arena: inputs in, one call, outputs against the first run's
+        const void *ag[8];
+        float *ap[2], *am[2], *av[2];
+        void *ao[2];
+        for (uint32_t l = 0; l < 2; ++l) {
+            uint64_t off, nb;
+            for (uint32_t r = 0; r < R; ++r) {
+                HZP(hzp_plan_arena_slice(plan, HZP_CLASS_BF16, R, HZP_GRAD_DEFAULT, variant, HZP_STREAM_GRAD, r, l, &off, &nb));
+                HIP(hipMemcpy(arena + off, hg[l][r].data(), nb, hipMemcpyHostToDevice));
+                ag[l * R + r] = arena + off;
+            }
+            HZP(hzp_plan_arena_slice(plan, HZP_CLASS_BF16, R, HZP_GRAD_DEFAULT, variant, HZP_STREAM_MASTER, 0, l, &off, &nb));
+            HIP(hipMemcpy(arena + off, hp0[l].data(), nb, hipMemcpyHostToDevice));
+            ap[l] = (float *)(arena + off);
+            HZP(hzp_plan_arena_slice(plan, HZP_CLASS_BF16, R, HZP_GRAD_DEFAULT, variant, HZP_STREAM_M, 0, l, &off, &nb));
+            HIP(hipMemcpy(arena + off, hm0[l].data(), nb, hipMemcpyHostToDevice));
+            am[l] = (float *)(arena + off);
+            HZP(hzp_plan_arena_slice(plan, HZP_CLASS_BF16, R, HZP_GRAD_DEFAULT, variant, HZP_STREAM_V, 0, l, &off, &nb));
+            HIP(hipMemcpy(arena + off, hv0[l].data(), nb, hipMemcpyHostToDevice));
+            av[l] = (float *)(arena + off);
+            HZP(hzp_plan_arena_slice(plan, HZP_CLASS_BF16, R, HZP_GRAD_DEFAULT, variant, HZP_STREAM_PARAM_OUT, 0, l, &off, &nb));
+            ao[l] = arena + off;
+        }
+        HZP(hzp_adamw_shard(plan, 0, 2, HZP_CLASS_BF16, rank, &hyper, ag, R, ap, am, av, ao, stream));
+        HIP(hipStreamSynchronize(stream));
+        for (uint32_t l = 0; l < 2; ++l) {
+            std::vector<float> got(b[l].s1), first(b[l].s1), gotv(b[l].s1), firstv(b[l].s1);
+            if (!to_host(got, ap[l]) || !to_host(first, dp[l]) || !to_host(gotv, av[l]) || !to_host(firstv, dv[l])) return 2;
+            if (memcmp(got.data(), first.data(), got.size() * 4) != 0 || memcmp(gotv.data(), firstv.data(), got.size() * 4) != 0) {
+                bad++;
+                printf("selftest: the update on arena slices differs from the update on separate buffers (layer %u)\n", l);
+            }
+        }
+        HIP(hipFree(raw));
+    }
+
     hzp_plan_free(plan);
     if (bad) {
         printf("selftest: %d mismatches\n", bad);
         return 1;
     }
-    printf("selftest ok: fused update of 2 layers (rank %u: j=%u k=%u i=%u), gathers, unpack, reduction\n", rank, j, k, i);
+    printf("selftest ok: fused update of 2 layers (rank %u: j=%u k=%u i=%u), gathers, unpack, reduction, arena and tuner\n", rank, j, k, i);
     return 0;
 }
