@@ -135,6 +135,61 @@ def test_one_shard_longer_than_a_launch():
     assert int((m == 0).sum().item()) <= int(((g[0].float() + g[1].float()) == 0).sum().item())
 
 
+def test_the_longest_shard_the_entry_points_accept():
+    """2^30 - 512 elements, the longest slice below the 2^30 limit of the kernels' 32-bit byte offsets (the
+    last fp32 quad lies 2 KiB below 4 GiB): update (seven launches), stand-alone reduction and a two-shard
+    gather into a 4 GiB bucket, sampled against the oracle at both ends, around every launch cut and every
+    power-of-two byte offset, and at random; whole outputs through device-side comparisons."""
+    n = (1 << 30) - 512
+    say("one shard of %d elements" % n)
+    gc.collect()
+    torch.cuda.empty_cache()
+    plan = hzp.hzp_plan([1], [n], 8, 1, 1)
+    assert plan.bucket(0, 0).s1 == n
+    bf16, f32 = torch.bfloat16, torch.float32
+    g = hzp_inputs.device_normal(n, 1e-3, 41, DEV, bf16, None, 0)
+    p = hzp_inputs.device_normal(n, 0.02, 43, DEV, f32, None, 0)
+    m, v = torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    out = torch.zeros(n, dtype=bf16, device=DEV)
+    rng = np.random.default_rng(9)
+    marks = [k * 300000 * 512 for k in range(1, 7)] + [1 << 26, 1 << 27, 1 << 28, 1 << 29, 3 << 28]
+    idx = np.unique(np.concatenate([np.arange(1024), np.arange(n - 1024, n), rng.integers(0, n, size=8192)] +
+                                   [np.arange(c - 600, c + 600) for c in marks]))
+    ti = torch.from_numpy(idx).to(DEV)
+    s = dict(g=to_host(_bits16(g)[ti], np.uint16), p=to_host(p[ti], np.float32).copy(),
+             m=np.zeros(idx.size, np.float32), v=np.zeros(idx.size, np.float32))
+    a = hzp_inputs.ADAMW
+    hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], 1.0, 1)
+    hzp.hzp_adamw_shard(plan, 0, 1, 0, 0, hy, [g], 1, [p], [m], [v], [out])
+    torch.cuda.synchronize()
+    on.adamw(on.reduce([s["g"]], scale=1.0), s["p"], s["m"], s["v"], step=1, **a)
+    for key, t in (("p", p), ("m", m), ("v", v)):
+        assert_close_f32(to_host(t[ti], np.float32), s[key], "longest shard " + key, key)
+    assert_cast_of(to_host(_bits16(out)[ti], np.uint16), to_host(p[ti], np.float32), "longest shard bf16")
+    # every element was updated: m = 0.1 g exactly where g is finite, so m is zero only where g is
+    assert int((m == 0).sum().item()) == int((g == 0).sum().item())
+    # stand-alone reduction of two slices of that length into v's buffer, bit for bit on the samples;
+    # the whole output against the same sum formed by the library of the tensors' operations
+    hzp.hzp_reduce_shard(plan, 0, 0, 1, 0, [g, out], 0.5, False, v)
+    torch.cuda.synchronize()
+    want = on.reduce([s["g"], to_host(_bits16(out)[ti], np.uint16)], scale=0.5)
+    assert np.array_equal(to_host(v[ti], np.uint32), want.view(np.uint32))
+    m.copy_(g)                              # exact in fp32: bf16 values and their sum of two, then one rounding by 0.5
+    m.add_(out)
+    m.mul_(0.5)
+    assert torch.equal(v, m)
+    del m, p
+    # two shards of that length gathered into one bucket of 2^31 - 1024 elements
+    plan2 = hzp.hzp_plan([1], [2 * n], 8, 2, 2)
+    assert plan2.bucket(0, 0).s3 == n
+    bucket = torch.empty(2 * n, dtype=torch.int16, device=DEV)
+    hzp.hzp_gather_layer(plan2, 0, 0, 3, [g, out], bucket, None)
+    torch.cuda.synchronize()
+    assert torch.equal(bucket[:n], _bits16(g)) and torch.equal(bucket[n:], _bits16(out))
+    tail, head = to_host(_bits16(g)[n - 64:], np.uint16).copy(), to_host(_bits16(out)[:64], np.uint16).copy()
+    assert np.array_equal(to_host(bucket[n - 64:n + 64], np.uint16), on.gather_concat([tail, head]))
+
+
 def test_moe_layer_sampled_and_unpacked():
     """One MoE layer: S1 = 71.4M elements at R = 16, then unpack into its 199 tensors."""
     w = _fused_sampled_parity(3, 1, steps=1)
