@@ -250,6 +250,54 @@ def test_irregular_mixed_classes_and_weight_decay_table(R):
         sim.compare("R=%d step %d" % (R, t))
 
 
+def test_degenerate_plans():
+    """No sharding at all (Z1 = Z3 = 1) on a one-element tensor; shards that hold nothing but padding
+    (one element spread over 8 ranks); layers that have no bucket of the class inside a layer-range call;
+    shards shorter than one workgroup's tile.  Update on every rank, then both gathers and the unpack."""
+    say("degenerate plans")
+    cases = [
+        (dict(tensors_per_layer=[1], tensor_numel=[1]), 8, 1, 1, 1),
+        (dict(tensors_per_layer=[1], tensor_numel=[1]), 8, 2, 8, 3),
+        (dict(tensors_per_layer=[1, 1, 2], tensor_numel=[5, 9, 1, 700], tensor_class=[1, 0, 1, 0],
+              tensor_wd_mult=[0.0, 1.0, 0.5, 1.0]), 8, 2, 4, 2),
+        (dict(tensors_per_layer=[3], tensor_numel=[1, 1, 1]), 16, 4, 4, 16),
+    ]
+    for desc, align, z3, z1, R in cases:
+        sim = Sim(desc, align, z3, z1, R, 1e-3, seed=21)
+        for t in (1, 2):
+            sim.step(t)
+            sim.compare("degenerate z1=%d step %d" % (z1, t))
+        oplan, plan = sim.oplan, sim.plan
+        K = oplan["K"]
+        for bi, b in enumerate(oplan["buckets"]):
+            if b["cls"] != 0:
+                continue
+            shards3, host3 = [], []
+            for j in range(z3):
+                owners = [sim.d[bi, j + z3 * k]["out"][1] for k in range(K)]
+                dst = torch.empty(b["S3"], dtype=torch.int16, device=DEV)
+                hzp.hzp_gather_layer(plan, b["layer"], 0, 1, owners, dst)
+                torch.cuda.synchronize()
+                want = on.gather_concat([to_host(o, np.uint16) for o in owners])
+                assert np.array_equal(to_host(dst, np.uint16), want)
+                shards3.append(dst)
+                host3.append(want)
+            full = torch.empty(b["P"], dtype=torch.int16, device=DEV)
+            touts = [torch.empty(oplan["tensors"][t]["numel"], dtype=torch.int16, device=DEV) for t in b["tensor_ids"]]
+            hzp.hzp_gather_layer(plan, b["layer"], 0, 3, shards3, full, touts)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_host(full, np.uint16), on.gather_concat(host3))
+            for t, tout in zip(b["tensor_ids"], touts):
+                rec = oplan["tensors"][t]
+                assert np.array_equal(to_host(tout, np.uint16), on.unpack_tensor(host3, rec["offset"], rec["numel"]))
+            # a shard of nothing but padding holds +0.0 everywhere after the update
+            for rank in sim.ranks:
+                beg, n = op.shard_range(oplan, b, 1, rank)
+                if beg >= b["payload_end"]:
+                    assert not to_host(sim.d[bi, rank]["out"][1], np.uint16).any()
+                    assert not to_host(sim.d[bi, rank]["p"][1], np.uint32).any()
+
+
 def test_uniform_decay_path_with_other_hyperparameters():
     say("fused, uniform decay, other hyper-parameters, no cast output")
     desc = hzp_inputs.irregular_desc(8, seed=77, max_numel=30000, tensors_per_layer=4, f32_every=0)
