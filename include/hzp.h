@@ -312,9 +312,9 @@ hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint3
  * last three with events on `stream`, and returns the variant with the shortest time (variant 0
  * unless another one is more than 0.5 % faster).  Call it once
  * after allocating the arena and before filling it: its contents are overwritten (each variant's
- * streams with ordinary non-zero values: all-zero gradients run 1-3 % faster than any others and hide
- * differences between the variants) and it is all zero on return (hzp_arena_tune is not for graph
- * capture).
+ * streams with ordinary non-zero values: on all-zero gradients and states the update runs 1-3 %
+ * faster than on any others and shows less of the differences between the variants) and it is all
+ * zero on return (hzp_arena_tune is not for graph capture).
  *   arena, arena_bytes : DEVICE allocation, start on a multiple of HZP_ARENA_ALIGN; it must hold
  *                        variant 0; to let every variant compete, allocate the largest of the
  *                        variants' totals (at most 63 units per stream more than variant 1)

@@ -299,8 +299,8 @@ extern "C" hzp_status_t hzp_gather_layers(const hzp_plan_t *plan, uint32_t layer
 
 // Times the fused update of all layers under every arena layout variant that fits the caller's
 // allocation and reports the fastest.  Each variant's streams are filled with ordinary non-zero
-// values first (the update runs 1-3 % faster on all-zero gradients than on any others, and then
-// shows less of the differences between the variants); the arena is all zero afterwards.
+// values first (on all-zero gradients and states the update runs 1-3 % faster than on any others,
+// and then shows less of the differences between the variants); the arena is all zero afterwards.
 extern "C" hzp_status_t hzp_arena_tune(const hzp_plan_t *plan, uint32_t cls, uint32_t rank, uint32_t R, void *arena,
                                        uint64_t arena_bytes, hipStream_t stream, uint32_t *best_variant,
                                        double *seconds)
