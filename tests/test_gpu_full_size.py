@@ -190,6 +190,44 @@ def test_the_longest_shard_the_entry_points_accept():
     assert np.array_equal(to_host(bucket[n - 64:n + 64], np.uint16), on.gather_concat([tail, head]))
 
 
+@pytest.mark.parametrize("R", [4, 16])
+def test_fp32_class_at_size_over_several_launches(R):
+    """Buckets of class F32 (fp32 gradients in, fp32 parameters out) at large shapes: three layers of
+    40, 70 and 170 M elements in one call (the last one longer than a launch), per-tensor decay
+    multipliers, two steps; sampled against the oracle at the ends, around the cuts and at random."""
+    sizes = [40_000_000 + 8, 70_000_000 + 24, 170_000_000]
+    say("fp32 class at size, R=%d" % R)
+    gc.collect()
+    torch.cuda.empty_cache()
+    plan = hzp.hzp_plan([1, 1, 1], sizes, 8, 1, 1, tensor_class=[1, 1, 1], tensor_wd_mult=[1.0, 0.0, 0.5])
+    f32 = torch.float32
+    rng = np.random.default_rng(17 + R)
+    a = hzp_inputs.ADAMW
+    g, p, m, v, out, samples = [], [], [], [], [], []
+    for l, n in enumerate(sizes):
+        assert plan.bucket(l, 1).s1 == n
+        gl = [hzp_inputs.device_normal(n, 1e-3, 500 + 31 * l + r, DEV, f32, None, 0) for r in range(R)]
+        g += gl
+        p.append(hzp_inputs.device_normal(n, 0.02, 900 + l, DEV, f32, None, 0))
+        m.append(torch.zeros(n, device=DEV)); v.append(torch.zeros(n, device=DEV)); out.append(torch.zeros(n, device=DEV))
+        cuts = [c for c in (300000 * 512,) if c < n]
+        idx = np.unique(np.concatenate([np.arange(1024), np.arange(n - 1024, n), rng.integers(0, n, size=6000)] +
+                                       [np.arange(c - 600, c + 600) for c in cuts]))
+        ti = torch.from_numpy(idx).to(DEV)
+        samples.append(dict(ti=ti, g=[to_host(x[ti], np.float32).copy() for x in gl], p=to_host(p[l][ti], np.float32).copy(),
+                            m=np.zeros(idx.size, np.float32), v=np.zeros(idx.size, np.float32),
+                            wd=np.full(idx.size, [1.0, 0.0, 0.5][l], np.float32)))
+    for step in (1, 2):
+        hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], 1.0 / R, step)
+        hzp.hzp_adamw_shard(plan, 0, 3, 1, 0, hy, g, R, p, m, v, out)
+        torch.cuda.synchronize()
+        for l, s in enumerate(samples):
+            on.adamw(on.reduce(s["g"], scale=1.0 / R), s["p"], s["m"], s["v"], step=step, wd_mult=s["wd"], out_bf16=False, **a)
+            for key, t in (("p", p[l]), ("m", m[l]), ("v", v[l])):
+                assert_close_f32(to_host(t[s["ti"]], np.float32), s[key], "fp32 class layer %d step %d %s" % (l, step, key), key)
+            assert torch.equal(out[l], p[l]), "fp32 output is the parameters themselves"
+
+
 def test_moe_layer_sampled_and_unpacked():
     """One MoE layer: S1 = 71.4M elements at R = 16, then unpack into its 199 tensors."""
     w = _fused_sampled_parity(3, 1, steps=1)
