@@ -228,6 +228,50 @@ def test_fp32_class_at_size_over_several_launches(R):
             assert torch.equal(out[l], p[l]), "fp32 output is the parameters themselves"
 
 
+def test_accumulation_flow_at_size():
+    """fp32 contributions of two micro-batches accumulated into resident fp32 gradient shards of 100 and
+    170 M elements (R = 8 per micro-batch), then the update from those shards (the R == 0 form) over
+    several launches; accumulator sampled bit for bit, update sampled within tolerance."""
+    sizes = [100_000_000 + 40, 170_000_000]
+    R, M = 8, 2
+    say("accumulation flow at size")
+    gc.collect()
+    torch.cuda.empty_cache()
+    plan = hzp.hzp_plan([1, 1], sizes, 8, 1, 1)
+    f32 = torch.float32
+    rng = np.random.default_rng(23)
+    a = hzp_inputs.ADAMW
+    acc, p, m, v, out, samples = [], [], [], [], [], []
+    for l, n in enumerate(sizes):
+        acc.append(torch.full((n,), 3.0, device=DEV))
+        p.append(hzp_inputs.device_normal(n, 0.02, 700 + l, DEV, f32, None, 0))
+        m.append(torch.zeros(n, device=DEV)); v.append(torch.zeros(n, device=DEV))
+        out.append(torch.zeros(n, dtype=torch.int16, device=DEV))
+        cuts = [c for c in (300000 * 512,) if c < n]
+        idx = np.unique(np.concatenate([np.arange(1024), np.arange(n - 1024, n), rng.integers(0, n, size=6000)] +
+                                       [np.arange(c - 600, c + 600) for c in cuts]))
+        samples.append(dict(ti=torch.from_numpy(idx).to(DEV), acc=np.zeros(idx.size, np.float32),
+                            p=to_host(p[l][torch.from_numpy(idx).to(DEV)], np.float32).copy(),
+                            m=np.zeros(idx.size, np.float32), v=np.zeros(idx.size, np.float32)))
+    for mb in range(M):
+        for l, n in enumerate(sizes):
+            g = [hzp_inputs.device_normal(n, 1e-3, 3000 + 100 * mb + 10 * l + r, DEV, f32, None, 0) for r in range(R)]
+            hzp.hzp_reduce_shard(plan, l, 0, 1, 0, g, 1.0 / R, mb > 0, acc[l], grad_dtype=hzp.HZP_GRAD_F32)
+            torch.cuda.synchronize()
+            s = samples[l]
+            on.reduce([to_host(x[s["ti"]], np.float32).copy() for x in g], scale=1.0 / R, accumulate=(mb > 0), out=s["acc"])
+            assert np.array_equal(to_host(acc[l][s["ti"]], np.uint32), s["acc"].view(np.uint32)), (mb, l)
+            del g
+    hy = hzp.adamw_hyper(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], 1.0 / M, 1)
+    hzp.hzp_adamw_shard(plan, 0, 2, 0, 0, hy, acc, 0, p, m, v, out)
+    torch.cuda.synchronize()
+    for l, s in enumerate(samples):
+        on.adamw(on.reduce([s["acc"]], scale=1.0 / M), s["p"], s["m"], s["v"], step=1, **a)
+        for key, t in (("p", p[l]), ("m", m[l]), ("v", v[l])):
+            assert_close_f32(to_host(t[s["ti"]], np.float32), s[key], "accumulated layer %d %s" % (l, key), key)
+        assert_cast_of(to_host(out[l][s["ti"]], np.uint16), to_host(p[l][s["ti"]], np.float32), "accumulated layer %d bf16" % l)
+
+
 def test_moe_layer_sampled_and_unpacked():
     """One MoE layer: S1 = 71.4M elements at R = 16, then unpack into its 199 tensors."""
     w = _fused_sampled_parity(3, 1, steps=1)
