@@ -272,6 +272,63 @@ def test_accumulation_flow_at_size():
         assert_cast_of(to_host(out[l][s["ti"]], np.uint16), to_host(p[l][s["ti"]], np.float32), "accumulated layer %d bf16" % l)
 
 
+def test_scheduler_at_layer_size():
+    """Ten 7B-class layers (405 MB buckets) through a three-slot pool, prefetched two ahead from the
+    background thread; then the same at parameter granularity (9 regions per layer) with one call per
+    layer.  Every gathered bucket and tensor is compared on the device with the shards it came from."""
+    say("scheduler at layer size")
+    cfg = hzp_inputs.config(1)
+    gc.collect()
+    torch.cuda.empty_cache()
+    n = 10
+    w = bench.Workload(cfg, n, cfg["z3"] + 1, torch, hzp, hzp_inputs, arena_variant="0")
+    consumer = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    whole = [torch.cat([_bits16(x) for x in w.keep[l][7]]) for l in range(n)]        # what each bucket must hold
+
+    class View:
+        def __init__(self, ptr, count):
+            self.__cuda_array_interface__ = {"shape": (count,), "typestr": "<i2", "data": (ptr, False), "version": 3}
+
+    ok = torch.ones((), dtype=torch.bool, device=DEV)
+    sched = hzp.Sched(w.plan, gather_slots=3, queue_capacity=8)
+    for l in range(2):
+        sched.prefetch(l, w.l3_args[l][1], consumer.cuda_stream)
+    for l in range(n):
+        ptr = sched.acquire(l, consumer.cuda_stream)
+        with torch.cuda.stream(consumer):
+            ok &= torch.equal(torch.as_tensor(View(ptr, whole[l].numel()), device=DEV), whole[l])
+        sched.release(l, consumer.cuda_stream)
+        if l + 2 < n:
+            sched.prefetch(l + 2, w.l3_args[l + 2][1], consumer.cuda_stream)
+    consumer.synchronize()
+    sched.drain()
+    assert bool(ok.item()) and sched.stats().gathers_issued == n
+    sched.destroy()
+    # parameter granularity, one call per layer
+    per_layer = max(b.n_tensors for b in w.buckets)
+    layer_bytes = max(2 * b.padded + 256 * b.n_tensors for b in w.buckets)
+    sched = hzp.Sched(w.plan, gather_slots=3 * per_layer, queue_capacity=6 * per_layer + 4, pool_bytes=3 * ((layer_bytes + 255) // 256 * 256))
+    first = [0]
+    for b in w.buckets:
+        first.append(first[-1] + b.n_tensors)
+    for l in range(2):
+        sched.prefetch_params(l, w.l3_args[l][1], consumer.cuda_stream)
+    for l in range(n):
+        ptrs = sched.acquire_params(l, w.buckets[l].n_tensors, consumer.cuda_stream)
+        with torch.cuda.stream(consumer):
+            for t, ptr in zip(range(first[l], first[l + 1]), ptrs):
+                rec = w.plan.tensor(t)
+                ok &= torch.equal(torch.as_tensor(View(ptr, rec.numel), device=DEV), whole[l][rec.offset:rec.offset + rec.numel])
+        sched.release_params(l, consumer.cuda_stream)
+        if l + 2 < n:
+            sched.prefetch_params(l + 2, w.l3_args[l + 2][1], consumer.cuda_stream)
+    consumer.synchronize()
+    sched.drain()
+    assert bool(ok.item()) and sched.stats().gathers_issued == first[n]
+    sched.destroy()
+
+
 def test_moe_layer_sampled_and_unpacked():
     """One MoE layer: S1 = 71.4M elements at R = 16, then unpack into its 199 tensors."""
     w = _fused_sampled_parity(3, 1, steps=1)
