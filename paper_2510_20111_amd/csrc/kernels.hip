@@ -773,7 +773,8 @@ hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t 
 {
     if (bytes_per_shard == 0) return HZP_OK;
     const uint64_t nvec = bytes_per_shard / 16;
-    if (nvec > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layer: shard larger than 64 GiB");
+    // (a grid holds fewer than 2^32 threads per dimension: one thread per vector, rounded up to whole wavefronts)
+    if (nvec > 0xFFFFFFFFull - kWave) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layer: shard of 64 GiB or more");
     ConcatArgs a{};
     uint32_t listed = 0;
     for (uint32_t s = 0; s < n_shards; ++s) {
@@ -806,7 +807,7 @@ hzp_status_t launch_concat_layers(const void *const *srcs, uint32_t per_layer, c
     }
     for (uint32_t l = 0; l < n_layers; ++l) {
         const uint64_t bytes = bytes_per_piece[l];
-        if (bytes / 16 > 0xFFFFFFFFull) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layers: shard larger than 64 GiB");
+        if (bytes / 16 > 0xFFFFFFFFull - kWave) return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_layers: shard of 64 GiB or more");
         if (bytes == 0) continue;
         for (uint32_t k = 0; k < per_layer; ++k) {
             const void *src = srcs[(size_t)l * per_layer + k];
@@ -843,7 +844,7 @@ hzp_status_t launch_concat_ranges(const void *const *srcs, const uint64_t *dst_o
     uint64_t tiles = 0, total = 0;
     bool uniform = true;
     for (uint32_t s = 0; s < n; ++s) {
-        if (bytes[s] / 16 > 0xFFFFFFFFull || dst_off[s] / 16 > 0xFFFFFFFFull)
+        if (bytes[s] / 16 > 0xFFFFFFFFull - kWave || dst_off[s] / 16 > 0xFFFFFFFFull)
             return fail(HZP_ERR_UNSUPPORTED, "hzp_gather_shard: shard larger than 64 GiB");
         a.src[s] = srcs[s];
         a.dst_vec[s] = (uint32_t)(dst_off[s] / 16);
