@@ -555,6 +555,38 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
         "compute": "spin", "gathers_per_pass": first[-1], "scheduled_ms": round(t_layer, 3),
         "gather_time_hidden": round((spin["serial_ms"] - t_layer) / t_gather, 3)}
     sched.destroy()
+
+    # Backward pass: each layer's gradient contributions are reduced as soon as its compute has produced
+    # them ("hungrily", Section 4.2): from the background thread on the scheduler's reduction stream, against
+    # the same reductions issued on the compute stream behind each layer's compute.
+    add_secondary_buffers(w, ["reduce"])
+    torch.cuda.synchronize()
+
+    def reduces_only():
+        for l, slices, dst, _ in w.reduce_args:
+            hzp.hzp_reduce_shard(w.plan, l, 0, 3, w.rank, slices, w.cfg["grad_scale"], False, dst, stream=s, R=w.R)
+
+    t_reduce = timed(reduces_only)
+
+    def serial_backward():
+        for l, slices, dst, _ in reversed(w.reduce_args):
+            compute(l)
+            hzp.hzp_reduce_shard(w.plan, l, 0, 3, w.rank, slices, w.cfg["grad_scale"], False, dst, stream=s, R=w.R)
+
+    sched = hzp.Sched(w.plan, gather_slots=1, queue_capacity=2 * n + 4)
+
+    def hungry_backward():
+        for l, slices, dst, _ in reversed(w.reduce_args):
+            compute(l)
+            sched.reduce(l, 3, w.rank, slices, w.cfg["grad_scale"], False, dst, s)
+        sched.join(s)
+
+    t_serial_b, t_hungry = timed(serial_backward), timed(hungry_backward)
+    sched.drain()
+    out["hungry_reduce"] = {"compute": "spin", "reduce_only_ms": round(t_reduce, 3), "serial_ms": round(t_serial_b, 3),
+                            "scheduled_ms": round(t_hungry, 3),
+                            "reduce_time_hidden": round((t_serial_b - t_hungry) / t_reduce, 3)}
+    sched.destroy()
     return out
 
 
