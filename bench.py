@@ -438,6 +438,12 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
         with torch.cuda.stream(stream):
             torch.matmul(a, b, out=c)
 
+    a_half, c_half = a[:2048], c[:2048]
+
+    def one_half_matmul():
+        with torch.cuda.stream(stream):
+            torch.matmul(a_half, b, out=c_half)
+
     def one_spin():
         with torch.cuda.stream(stream):
             torch.cuda._sleep(1000000)
@@ -445,6 +451,7 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
     t_gather = timed(gathers_only)
     per_layer = compute_ratio * t_gather / n
     reps = max(1, int(round(per_layer / timed(one_matmul))))
+    reps_half = max(1, int(round(per_layer / timed(one_half_matmul))))
     cycles = int(1000000 * per_layer / timed(one_spin))
 
     def make_compute(kind):
@@ -453,12 +460,15 @@ def overlap_probe(w, hzp, torch, stream, depth=2, rounds=5, compute_ratio=4.0):
                 if kind == "gemm":
                     for _ in range(reps):
                         torch.matmul(a, b, out=c)
+                elif kind == "gemm_half":          # 2048 x 4096 x 4096: tiles for about half of the CUs
+                    for _ in range(reps_half):
+                        torch.matmul(a_half, b, out=c_half)
                 else:
                     torch.cuda._sleep(cycles)
         return compute
 
     out = {"layers": n, "prefetch_depth": depth, "gather_only_ms": round(t_gather, 3), "cases": []}
-    for kind in ("spin", "gemm"):
+    for kind in ("spin", "gemm", "gemm_half"):
         compute = make_compute(kind)
 
         def compute_only():
