@@ -749,6 +749,23 @@ def fused_launch_count(w):
     return launches + (1 if cnt else 0)
 
 
+def roofline_entry(np, kernel, algo_bytes, ms, launches, key, step_kernel_ms=None, per_step=None):
+    """One kernel's roofline object: `ms` is the average time of its `launches` launches in a step (or
+    secondary pass), `algo_bytes` what they move together; `per_step` the same time for each timed step."""
+    per_launch_ms = ms / launches
+    ach = algo_bytes / launches / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
+    out = {"kernel": kernel, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+           "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": read_traffic(key),
+           "traffic_key": key, "launches_per_step": launches, "avg_launch_us": round(per_launch_ms * 1e3, 2),
+           "algorithmic_bytes_per_launch": algo_bytes / launches}
+    if step_kernel_ms is not None:
+        out["share_of_step_time"] = round(ms / max(step_kernel_ms, 1e-9), 3)
+    if per_step is not None:        # over the timed steps (each step's launches of the kernel bracketed by one event pair)
+        out["median_launch_us"] = round(float(np.median(per_step)) / launches * 1e3, 2)
+        out["min_launch_us"] = round(float(per_step.min()) / launches * 1e3, 2)
+    return out
+
+
 def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=False):
     """Builds workload `idx`, runs warmup + steps of the whole step and returns its figures."""
     cfg = hzp_inputs.config(idx)
@@ -786,17 +803,8 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
     fused_bytes = (26 + 2 * R) * w.s1_total
     g1_bytes, g3_bytes = 4 * w.s3_total, 4 * w.p_total
 
-    def roof(kernel, algo_bytes, ms, launches, key, per_step=None):
-        per_launch_ms = ms / launches
-        ach = algo_bytes / launches / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
-        return {"kernel": kernel, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": read_traffic(key),
-                "traffic_key": key, "launches_per_step": launches, "avg_launch_us": round(per_launch_ms * 1e3, 2),
-                "algorithmic_bytes_per_launch": algo_bytes / launches,
-                "share_of_step_time": round(ms / max(fused_ms + g1_ms + g3_ms, 1e-9), 3),
-                # over the timed steps (each step's launches of the kernel bracketed by one event pair)
-                "median_launch_us": None if per_step is None else round(float(np.median(per_step)) / launches * 1e3, 2),
-                "min_launch_us": None if per_step is None else round(float(per_step.min()) / launches * 1e3, 2)}
+    def roof(kernel, algo_bytes, ms, launches, key, per_step):
+        return roofline_entry(np, kernel, algo_bytes, ms, launches, key, fused_ms + g1_ms + g3_ms, per_step)
 
     fused_launches = fused_launch_count(w)
     rooflines = {}
@@ -906,13 +914,8 @@ def main():
     }
     fused_bytes, fused_launches = t["fused_bytes"], t["fused_launches"]
 
-    def roof(kernel, algo_bytes, ms, launches, key, per_step=None):
-        per_launch_ms = ms / launches
-        ach = algo_bytes / launches / (per_launch_ms * 1e-3) / 1e9 if ms > 0 else 0.0
-        return {"kernel": kernel, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": read_traffic(key),
-                "traffic_key": key, "launches_per_step": launches, "avg_launch_us": round(per_launch_ms * 1e3, 2),
-                "algorithmic_bytes_per_launch": algo_bytes / launches}
+    def roof(kernel, algo_bytes, ms, launches, key):
+        return roofline_entry(np, kernel, algo_bytes, ms, launches, key)
 
     secondary = [x for x in args.secondary.split(",") if x]
     if "overlap" in secondary:
