@@ -118,3 +118,78 @@ def test_fused_update_on_arena_slices_matches_the_oracle(variant):
                 assert_close_f32(to_host(dev[l][key], np.float32), ora[l][key], tag + " " + key, key)
             assert_cast_of(to_host(dev[l]["o"], np.uint16), to_host(dev[l]["p"], np.float32), tag + " bf16")
         assert not arena[~touched].any().item(), "a gap between the streams was written"
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_plans_on_the_arena(seed):
+    """Small random plans (free group sizes, both classes, decay multipliers, tiny tensors): every stream
+    of a class at the planner's offsets of a random variant, the tuner run on the allocation first, one
+    update over all layers, against the oracle; the gaps between the streams stay zero."""
+    from test_gpu_random_plans import _draw
+    from gpu_util import wd_mult_array
+    rng = np.random.default_rng(7000 + seed)
+    d = _draw(rng)
+    say("random plan on the arena %d: %s" % (seed, {k: d[k] for k in ("tensors_per_layer", "align", "z1", "z2", "z3")}))
+    args = (d["tensors_per_layer"], d["tensor_numel"], d["align"], d["z3"], d["z1"], d["z2"])
+    kw = dict(tensor_class=d["tensor_class"], tensor_wd_mult=d["tensor_wd_mult"])
+    oplan, plan = op.make_plan(*args, **kw), hzp.hzp_plan(*args, **kw)
+    R = int(rng.choice([1, 2, 3, 4, 8]))
+    rank = int(rng.integers(0, oplan["world"]))
+    variant = int(rng.integers(0, hzp.HZP_ARENA_VARIANTS))
+    n_layers = oplan["n_layers"]
+    for cls in (0, 1):
+        buckets = [b for b in oplan["buckets"] if b["cls"] == cls]
+        if not buckets:
+            continue
+        gb = 4 if cls == 1 else 2
+        total, slices = op.arena_layout(oplan, cls, R, gb, variant)
+        assert plan.arena(cls, R, variant=variant) == total
+        whole, arena = aligned_arena(max(total, plan.arena(cls, R)))
+        best, secs = plan.arena_tune(cls, rank, R, arena, arena.numel())
+        assert 0 <= best < hzp.HZP_ARENA_VARIANTS and secs[0] > 0 and not arena.any().item()
+        gdt, odt = (torch.float32, torch.float32) if cls == 1 else (torch.int16, torch.int16)
+
+        def view(kind, index, layer, dtype):
+            off, nbytes = plan.arena_slice(cls, R, kind, index, layer, variant=variant)
+            assert (off, nbytes) == slices[kind, index, layer]
+            return arena[off:off + nbytes].view(dtype)
+
+        g, p, m, v, o, host = [], [], [], [], [], {}
+        for layer in range(n_layers):
+            b = op.find_bucket(oplan, layer, cls)
+            if b is None:
+                g += [0] * R
+                p.append(0); m.append(0); v.append(0); o.append(0)
+                continue
+            beg, n = op.shard_range(oplan, b, 1, rank)
+            ranges = payload_ranges(oplan, b)
+            p0 = np.ascontiguousarray(hzp_inputs.master_bucket(seed, layer, b["P"], ranges, cls)[beg:beg + n])
+            gs = [np.ascontiguousarray(hzp_inputs.grad_bucket(seed, 1, layer, r, b["P"], ranges, 1e-3, cls)[beg:beg + n])
+                  for r in range(R)]
+            gv = [view(hzp.HZP_STREAM_GRAD, r, layer, gdt) for r in range(R)]
+            for r in range(R):
+                gv[r].copy_(to_dev(gs[r]))
+            pv = view(STREAMS["p"], 0, layer, torch.float32)
+            pv.copy_(to_dev(p0))
+            g += gv
+            p.append(pv); m.append(view(STREAMS["m"], 0, layer, torch.float32)); v.append(view(STREAMS["v"], 0, layer, torch.float32))
+            o.append(view(STREAMS["o"], 0, layer, odt))
+            host[layer] = dict(p=p0, g=gs, wd=wd_mult_array(oplan, b, beg, n) if d["tensor_wd_mult"] else None, n=n)
+        hy = hzp.adamw_hyper(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], 1.0 / R, 2)
+        hzp.hzp_adamw_shard(plan, 0, n_layers, cls, rank, hy, g, R, p, m, v, o)
+        torch.cuda.synchronize()
+        touched = torch.zeros(arena.numel(), dtype=torch.bool, device=DEV)
+        for off, nbytes in slices.values():
+            touched[off:off + nbytes] = True
+        assert not arena[~touched].any().item(), "a gap between the streams was written"
+        for layer, h in host.items():
+            po, mo, vo = h["p"].copy(), np.zeros(h["n"], np.float32), np.zeros(h["n"], np.float32)
+            on.adamw(on.reduce(h["g"], scale=1.0 / R), po, mo, vo, step=2, wd_mult=h["wd"], out_bf16=(cls == 0), **HP)
+            tag = "seed %d class %d layer %d" % (seed, cls, layer)
+            assert_close_f32(to_host(p[layer], np.float32), po, tag + " p", "p")
+            assert_close_f32(to_host(m[layer], np.float32), mo, tag + " m", "m")
+            assert_close_f32(to_host(v[layer], np.float32), vo, tag + " v", "v")
+            if cls == 0:
+                assert_cast_of(to_host(o[layer], np.uint16), to_host(p[layer], np.float32), tag + " bf16")
+            else:
+                assert np.array_equal(to_host(o[layer], np.uint32), to_host(p[layer], np.uint32)), tag + " fp32 copy"
