@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=-1,
                     help="time only workload 0..4 (tiny, dense7b, dense70b, moe, irregular); default: headline on "
                          "moe, then the other four under \"configs\"")
-    ap.add_argument("--other-steps", type=int, default=10, help="timed steps of each non-headline workload")
+    ap.add_argument("--other-steps", type=int, default=20, help="timed steps of each non-headline workload")
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
