@@ -811,6 +811,22 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
     if "fused" in phases:
         rooflines["fused_adamw"] = roof("fused_adamw_kernel<R=%d,bf16>" % R, fused_bytes, fused_ms,
                                         fused_launches, "fused_adamw_%s" % cfg["name"], ph[:, 0])
+        # context, outside the timed steps: the update alone, call after call (inside the step it starts behind
+        # the level-3 gather's trailing writes)
+        alone = 10
+        for _ in range(2):
+            run_step(w, hzp, step, stream, {"fused"})
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(alone):
+            run_step(w, hzp, step, stream, {"fused"})
+        e1.record(stream)
+        stream.synchronize()
+        alone_ms = e0.elapsed_time(e1) / alone
+        rooflines["fused_adamw"]["alone_back_to_back"] = {
+            "achieved": round(fused_bytes / (alone_ms * 1e-3) / 1e9, 1) if alone_ms > 0 else 0.0,
+            "frac": round(fused_bytes / (alone_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if alone_ms > 0 else 0.0,
+            "avg_launch_us": round(alone_ms / fused_launches * 1e3, 2), "calls": alone}
     if "gather1" in phases:
         if w.l1_per_layer:
             rooflines["gather_level1"] = roof("concat_kernel (K=%d x S1 -> S3)" % w.K, g1_bytes, g1_ms,
@@ -853,7 +869,7 @@ def workload_text(t):
 def triple(t):
     """The {fused, gather1, gather3} rooflines of a timed workload, for the per-workload map."""
     r = t["rooflines"]
-    short = lambda x: None if x is None else {k: x[k] for k in ("kernel", "achieved", "frac", "avg_launch_us", "median_launch_us", "min_launch_us",
+    short = lambda x: None if x is None else {k: x[k] for k in x if k in ("kernel", "achieved", "frac", "avg_launch_us", "median_launch_us", "min_launch_us", "alone_back_to_back",
                                                                "launches_per_step", "algorithmic_bytes_per_launch",
                                                                "traffic", "traffic_key")}
     return {"workload": workload_text(t), "steps": t["steps"], "ms_per_step": round(t["ms_per_step"], 4),
