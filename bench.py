@@ -838,7 +838,12 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
     if "gather3" in phases:
         rooflines["gather_level3"] = roof("concat_kernel (Z3=%d x S3 -> P)" % w.z3, g3_bytes, g3_ms,
                                           w.n_layers, "concat_l3_%s" % cfg["name"], ph[:, 2])
+    # the launch-bound workloads also as one captured step replayed (context; the timed steps are issued call by call)
+    graph = None
+    if cfg["name"] in ("tiny", "irregular") and phases == {"fused", "gather1", "gather3"}:
+        graph = graph_probe(w, hzp, torch, stream, phases, max(steps, 20), warmup)
     out = {
+        "graph_replay": graph,
         "cfg": cfg, "w": w if keep else None, "stream": stream if keep else None, "rank": rank, "phases": phases,
         "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "rooflines": rooflines,
         "fused_ms": fused_ms, "g1_ms": g1_ms, "g3_ms": g3_ms, "fused_bytes": fused_bytes,
@@ -875,6 +880,7 @@ def triple(t):
     return {"workload": workload_text(t), "steps": t["steps"], "ms_per_step": round(t["ms_per_step"], 4),
             "shard_params_per_step": t["s1_total"],
             "arena_variant": t["arena_variant"], "arena_tune_GBps": t["arena_tune_GBps"],
+            "graph_replay": t["graph_replay"],
             "fused_update_params_per_s": t["s1_total"] / (t["fused_ms"] * 1e-3) if t["fused_ms"] > 0 else None,
             "fused": short(r.get("fused_adamw")), "gather1": short(r.get("gather_level1")),
             "gather3": short(r.get("gather_level3"))}
