@@ -306,6 +306,24 @@ hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint3
                              uint32_t R, float *const *master, float *const *m, float *const *v,
                              void *const *param_out, hipStream_t stream);
 
+/* The update with the step's hyper-parameters in DEVICE memory, for callers that capture their step
+ * in a HIP graph once and replay it every training step: hzp_adamw_shard bakes its hyper-parameters
+ * (the step number among them) into the launches it enqueues, hzp_adamw_shard_dev makes the kernels
+ * read them when they run.  hzp_adamw_scalars derives, on the host, the 48-byte block the kernels read
+ * (the bias corrections 1/(1-beta^step) in double precision, as hzp_adamw_shard does); the caller
+ * copies it to `scalars` before each replay (any copy that is ordered before the launches).  Same
+ * arithmetic, same results bit for bit, same arguments and errors otherwise.
+ *   scalars : DEVICE pointer, 16-byte aligned, valid until the launches have run
+ * Errors of hzp_adamw_scalars: INVALID_ARG (NULL, step 0). */
+typedef struct {
+    float f[12];
+} hzp_adamw_scalars_t;
+hzp_status_t hzp_adamw_scalars(const hzp_adamw_t *hyper, hzp_adamw_scalars_t *out);
+hzp_status_t hzp_adamw_shard_dev(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, uint32_t cls,
+                                 uint32_t rank, const hzp_adamw_scalars_t *scalars, const void *const *grad_slices,
+                                 uint32_t R, float *const *master, float *const *m, float *const *v,
+                                 void *const *param_out, hipStream_t stream);
+
 /* Set-up time choice of the arena layout variant (see hzp_plan_arena) for the fused update of
  * Section 4.1.2's optimizer step: runs hzp_adamw_shard over all layers of the class, with the
  * streams placed by each variant whose total fits arena_bytes, four times per variant, timing the

@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     HZP_OK, HZP_ERR_INVALID_ARG, HZP_ERR_RANGE, HZP_ERR_UNSUPPORTED, HZP_ERR_ALIGN,
     HZP_ERR_NOMEM, HZP_ERR_HIP,
     EXPORTS, LIB_PATH, HzpError, Plan, Sched, adamw_hyper, ptr_array,
-    hzp_plan, hzp_plan_free, hzp_memory_model, hzp_choose_groups, hzp_reduce_shard, hzp_adamw_shard, hzp_gather_layer, hzp_gather_layer_static, hzp_gather_layers, hzp_gather_shard, hzp_gather_tensor,
+    hzp_plan, hzp_plan_free, hzp_memory_model, hzp_choose_groups, hzp_reduce_shard, hzp_adamw_shard, hzp_adamw_scalars, hzp_adamw_shard_dev, hzp_gather_layer, hzp_gather_layer_static, hzp_gather_layers, hzp_gather_shard, hzp_gather_tensor,
     hzp_last_error,
 )

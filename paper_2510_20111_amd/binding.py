@@ -26,7 +26,7 @@ _STATUS_NAMES = ["HZP_OK", "HZP_ERR_INVALID_ARG", "HZP_ERR_RANGE", "HZP_ERR_UNSU
 
 EXPORTS = ["hzp_plan", "hzp_plan_free", "hzp_plan_prepare", "hzp_plan_info", "hzp_plan_bucket", "hzp_plan_tensor",
            "hzp_plan_rank", "hzp_plan_index", "hzp_plan_cover", "hzp_plan_shard", "hzp_plan_bytes",
-           "hzp_plan_arena", "hzp_plan_arena_slice", "hzp_arena_tune",
+           "hzp_plan_arena", "hzp_plan_arena_slice", "hzp_arena_tune", "hzp_adamw_scalars", "hzp_adamw_shard_dev",
            "hzp_reduce_shard", "hzp_adamw_shard", "hzp_gather_layer", "hzp_gather_layer_static", "hzp_gather_layers", "hzp_gather_shard", "hzp_gather_tensor", "hzp_last_error",
            "hzp_memory_model", "hzp_choose_groups",
            "hzp_sched_create", "hzp_sched_destroy", "hzp_sched_prefetch", "hzp_sched_prefetch_ahead", "hzp_sched_acquire",
@@ -93,6 +93,10 @@ class AdamW(ctypes.Structure):
                 ("grad_scale", ctypes.c_float), ("step", ctypes.c_uint32)]
 
 
+class AdamWScalars(ctypes.Structure):
+    _fields_ = [("f", ctypes.c_float * 12)]
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError("libhzp.so is not built: run `python paper_2510_20111_amd/build.py` "
@@ -144,6 +148,10 @@ def _load():
     L.hzp_adamw_shard.restype = ctypes.c_int
     L.hzp_adamw_shard.argtypes = [vp, u32, u32, u32, u32, ctypes.POINTER(AdamW), vp, u32,
                                   vp, vp, vp, vp, vp]
+    L.hzp_adamw_scalars.restype = ctypes.c_int
+    L.hzp_adamw_scalars.argtypes = [ctypes.POINTER(AdamW), ctypes.POINTER(AdamWScalars)]
+    L.hzp_adamw_shard_dev.restype = ctypes.c_int
+    L.hzp_adamw_shard_dev.argtypes = [vp, u32, u32, u32, u32, vp, vp, u32, vp, vp, vp, vp, vp]
     L.hzp_gather_layer.restype = ctypes.c_int
     L.hzp_gather_layer.argtypes = [vp, u32, u32, ctypes.c_int, vp, u32, vp, vp, vp]
     L.hzp_gather_layer_static.restype = ctypes.c_int
@@ -358,6 +366,22 @@ def hzp_adamw_shard(plan, layer_begin, layer_end, cls, rank, hyper, grad_slices,
                               ptr_array(grad_slices), R, ptr_array(master), ptr_array(m),
                               ptr_array(v), ptr_array(param_out) if param_out is not None else None,
                               _stream(stream)))
+
+
+def hzp_adamw_scalars(hyper):
+    """The 48-byte block hzp_adamw_shard_dev reads from device memory, as 12 floats (a list)."""
+    out = AdamWScalars()
+    _check(_L.hzp_adamw_scalars(ctypes.byref(hyper) if hyper is not None else None, ctypes.byref(out)))
+    return list(out.f)
+
+
+def hzp_adamw_shard_dev(plan, layer_begin, layer_end, cls, rank, scalars, grad_slices, R, master, m, v,
+                        param_out, stream=None):
+    """`scalars`: device tensor (or address) holding hzp_adamw_scalars' 12 floats."""
+    _check(_L.hzp_adamw_shard_dev(plan.handle, layer_begin, layer_end, cls, rank, _addr(scalars),
+                                  ptr_array(grad_slices), R, ptr_array(master), ptr_array(m),
+                                  ptr_array(v), ptr_array(param_out) if param_out is not None else None,
+                                  _stream(stream)))
 
 
 def hzp_gather_layer(plan, layer, cls, level, shard_ptrs, bucket_out=None, tensor_out=None,

@@ -3,6 +3,8 @@
 // kernels themselves trust their arguments.
 #include <hip/hip_runtime_api.h>
 
+#include <cmath>
+#include <cstring>
 #include <vector>
 
 #include "hzp_internal.hpp"
@@ -44,23 +46,43 @@ extern "C" hzp_status_t hzp_reduce_shard(const hzp_plan_t *plan, uint32_t layer,
     return launch_reduce(g32, grad_slices, R, n, scale, accumulate, out_f32, stream);
 }
 
-extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
-                                        uint32_t cls, uint32_t rank, const hzp_adamw_t *hy,
-                                        const void *const *grad_slices, uint32_t R, float *const *master,
-                                        float *const *m, float *const *v, void *const *param_out,
-                                        hipStream_t stream)
+// The step's scalars as the kernels take them; the bias corrections are formed in double.
+static AdamScalars derive_scalars(const hzp_adamw_t &hy)
 {
-    if (!plan || !hy || !grad_slices || !master || !m || !v)
-        return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: NULL plan, hyper-parameters or pointer array");
+    AdamScalars h;
+    h.lr = hy.lr;
+    h.beta1 = hy.beta1;
+    h.beta2 = hy.beta2;
+    h.one_minus_beta1 = 1.0f - hy.beta1;
+    h.one_minus_beta2 = 1.0f - hy.beta2;
+    h.eps = hy.eps;
+    h.weight_decay = hy.weight_decay;
+    h.grad_scale = hy.grad_scale;
+    h.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)hy.beta1, (double)hy.step)));
+    h.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)hy.beta2, (double)hy.step)));
+    return h;
+}
+
+// Argument checks and segment list shared by the two forms of the update; `hy` or `scalars_dev` is given.
+static hzp_status_t adamw_shard(const char *who, const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                                uint32_t cls, uint32_t rank, const hzp_adamw_t *hy,
+                                const hzp_adamw_scalars_t *scalars_dev, const void *const *grad_slices, uint32_t R,
+                                float *const *master, float *const *m, float *const *v, void *const *param_out,
+                                hipStream_t stream)
+{
+    if (!plan || (!hy && !scalars_dev) || !grad_slices || !master || !m || !v)
+        return fail(HZP_ERR_INVALID_ARG, "%s: NULL plan, hyper-parameters or pointer array", who);
     if (layer_begin >= layer_end)
-        return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: empty layer range [%u, %u)", layer_begin, layer_end);
+        return fail(HZP_ERR_INVALID_ARG, "%s: empty layer range [%u, %u)", who, layer_begin, layer_end);
     if (layer_end > plan->n_layers)
-        return fail(HZP_ERR_RANGE, "hzp_adamw_shard: layer_end %u of %u", layer_end, plan->n_layers);
-    if (cls > 1) return fail(HZP_ERR_RANGE, "hzp_adamw_shard: class %u", cls);
-    if (rank >= plan->world) return fail(HZP_ERR_RANGE, "hzp_adamw_shard: rank %u of %u", rank, plan->world);
-    if (hy->step == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: step is 1-based");
+        return fail(HZP_ERR_RANGE, "%s: layer_end %u of %u", who, layer_end, plan->n_layers);
+    if (cls > 1) return fail(HZP_ERR_RANGE, "%s: class %u", who, cls);
+    if (rank >= plan->world) return fail(HZP_ERR_RANGE, "%s: rank %u of %u", who, rank, plan->world);
+    if (hy && hy->step == 0) return fail(HZP_ERR_INVALID_ARG, "%s: step is 1-based", who);
+    if (scalars_dev && !aligned16(scalars_dev))
+        return fail(HZP_ERR_ALIGN, "%s: the scalars are not 16-byte aligned", who);
     if (R > HZP_MAX_REPLICAS)
-        return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: R=%u exceeds %u", R, HZP_MAX_REPLICAS);
+        return fail(HZP_ERR_UNSUPPORTED, "%s: R=%u exceeds %u", who, R, HZP_MAX_REPLICAS);
     const bool prereduced = (R == 0);
     const uint32_t per_layer = prereduced ? 1u : R;
     const bool g32 = prereduced || cls == HZP_CLASS_F32;
@@ -71,7 +93,7 @@ extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_b
     try {
         segs.reserve(layer_end - layer_begin);
     } catch (const std::bad_alloc &) {
-        return fail(HZP_ERR_NOMEM, "hzp_adamw_shard: out of host memory");
+        return fail(HZP_ERR_NOMEM, "%s: out of host memory", who);
     }
     for (uint32_t layer = layer_begin; layer < layer_end; ++layer) {
         const BucketRec *b = find_bucket(plan, layer, cls);
@@ -88,23 +110,56 @@ extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_b
         f.n_tensors = b->n_tensors;
         f.shard_begin = shard_index * b->S1;
         if (f.n >= (1ull << 30))
-            return fail(HZP_ERR_UNSUPPORTED, "hzp_adamw_shard: layer %u: shard of 2^30 elements or more", layer);
+            return fail(HZP_ERR_UNSUPPORTED, "%s: layer %u: shard of 2^30 elements or more", who, layer);
         if (!f.master || !f.m || !f.v)
-            return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: layer %u: NULL state pointer", layer);
+            return fail(HZP_ERR_INVALID_ARG, "%s: layer %u: NULL state pointer", who, layer);
         if (!aligned16(f.master) || !aligned16(f.m) || !aligned16(f.v) || !aligned16(f.out))
-            return fail(HZP_ERR_ALIGN, "hzp_adamw_shard: layer %u: state or output not 16-byte aligned", layer);
+            return fail(HZP_ERR_ALIGN, "%s: layer %u: state or output not 16-byte aligned", who, layer);
         if (param_out && !f.out)
-            return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: layer %u: NULL output pointer", layer);
+            return fail(HZP_ERR_INVALID_ARG, "%s: layer %u: NULL output pointer", who, layer);
         for (uint32_t r = 0; r < per_layer; ++r) {
             if (!f.grads[r])
-                return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard: layer %u: slice %u is NULL", layer, r);
+                return fail(HZP_ERR_INVALID_ARG, "%s: layer %u: slice %u is NULL", who, layer, r);
             if (!aligned16(f.grads[r]))
-                return fail(HZP_ERR_ALIGN, "hzp_adamw_shard: layer %u: slice %u not 16-byte aligned", layer, r);
+                return fail(HZP_ERR_ALIGN, "%s: layer %u: slice %u not 16-byte aligned", who, layer, r);
         }
         segs.push_back(f);
     }
     if (segs.empty()) return HZP_OK;
-    return launch_fused(plan, g32, o32, per_layer, segs.data(), segs.size(), *hy, stream);
+    if (hy) return launch_fused(plan, g32, o32, per_layer, segs.data(), segs.size(), derive_scalars(*hy), stream);
+    return launch_fused_dev(plan, g32, o32, per_layer, segs.data(), segs.size(),
+                            reinterpret_cast<const AdamScalars *>(scalars_dev), stream);
+}
+
+extern "C" hzp_status_t hzp_adamw_shard(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                                        uint32_t cls, uint32_t rank, const hzp_adamw_t *hy,
+                                        const void *const *grad_slices, uint32_t R, float *const *master,
+                                        float *const *m, float *const *v, void *const *param_out,
+                                        hipStream_t stream)
+{
+    return adamw_shard("hzp_adamw_shard", plan, layer_begin, layer_end, cls, rank, hy, nullptr, grad_slices, R, master, m,
+                       v, param_out, stream);
+}
+
+extern "C" hzp_status_t hzp_adamw_scalars(const hzp_adamw_t *hy, hzp_adamw_scalars_t *out)
+{
+    if (!hy || !out) return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_scalars: NULL argument");
+    if (hy->step == 0) return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_scalars: step is 1-based");
+    const AdamScalars h = derive_scalars(*hy);
+    std::memset(out, 0, sizeof *out);
+    std::memcpy(out, &h, sizeof h);
+    return HZP_OK;
+}
+
+extern "C" hzp_status_t hzp_adamw_shard_dev(const hzp_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                                            uint32_t cls, uint32_t rank, const hzp_adamw_scalars_t *scalars,
+                                            const void *const *grad_slices, uint32_t R, float *const *master,
+                                            float *const *m, float *const *v, void *const *param_out,
+                                            hipStream_t stream)
+{
+    if (!scalars) return fail(HZP_ERR_INVALID_ARG, "hzp_adamw_shard_dev: NULL scalars");
+    return adamw_shard("hzp_adamw_shard_dev", plan, layer_begin, layer_end, cls, rank, nullptr, scalars, grad_slices, R,
+                       master, m, v, param_out, stream);
 }
 
 extern "C" hzp_status_t hzp_gather_layer(const hzp_plan_t *plan, uint32_t layer, uint32_t cls, int level,

@@ -92,11 +92,21 @@ struct FusedSegment {
     uint64_t shard_begin;       // bucket position of element 0
 };
 
+// The scalars of one step as the update kernels take them.
+struct AdamScalars {
+    float lr, beta1, beta2, one_minus_beta1, one_minus_beta2, eps, weight_decay, grad_scale;
+    float inv_bc1, inv_bc2;     // 1/(1-beta1^t), 1/(1-beta2^t), computed in double on the host
+};
+static_assert(sizeof(AdamScalars) <= sizeof(hzp_adamw_scalars_t), "the public block holds the scalars");
+
 // Launchers; their arguments have been validated by the entry points.
 hzp_status_t launch_reduce(bool g32, const void *const *slices, uint32_t R, uint64_t n, float scale,
                            int accumulate, float *out, hipStream_t stream);
 hzp_status_t launch_fused(const hzp_plan_t *plan, bool g32, bool o32, uint32_t R, const FusedSegment *segs,
-                          size_t nseg, const hzp_adamw_t &hy, hipStream_t stream);
+                          size_t nseg, const AdamScalars &h, hipStream_t stream);
+// The same with the step's scalars read from device memory at run time (as packed by pack_scalars).
+hzp_status_t launch_fused_dev(const hzp_plan_t *plan, bool g32, bool o32, uint32_t R, const FusedSegment *segs,
+                              size_t nseg, const AdamScalars *scalars_dev, hipStream_t stream);
 hzp_status_t launch_concat(const void *const *srcs, uint32_t n_shards, uint64_t bytes_per_shard, void *dst,
                            hipStream_t stream);
 // Concatenates `per_layer` equal pieces for each of n_layers layers; srcs[l*per_layer + k], dsts[l].

@@ -255,10 +255,13 @@ __global__ __launch_bounds__(kWave) void reduce_kernel(const ReduceArgs a)
 // ---------------------------------------------------------------------------------------
 // Fused reduce + scale + AdamW + cast over many shard segments (one per layer bucket).
 // ---------------------------------------------------------------------------------------
-struct AdamScalars {
-    float lr, beta1, beta2, one_minus_beta1, one_minus_beta2, eps, weight_decay, grad_scale;
-    float inv_bc1, inv_bc2;     // 1/(1-beta1^t), 1/(1-beta2^t), computed in double on the host
+// Where a launch finds the step's scalars: in its argument block, or in device memory (a captured
+// launch then takes each replay's values from there).
+struct ScalarsInMemory {
+    const AdamScalars *p;
 };
+__device__ __forceinline__ const AdamScalars &scalars_of(const AdamScalars &h) { return h; }
+__device__ __forceinline__ AdamScalars scalars_of(const ScalarsInMemory &h) { return *h.p; }
 
 // Segment table in the kernel-argument block.  Segment s owns workgroups
 // [blk_end[s-1], blk_end[s]) and the pointers ptr[s*(R+4) ...]: R gradient slices, master,
@@ -388,8 +391,8 @@ __device__ __forceinline__ void fused_group(const void *const *sp, uint32_t R, c
 // in flight.  Measured optimum on MI355X: 4-6 wavefronts per CU.
 constexpr unsigned kFusedLdsBytes = 32768;
 
-template <int R_T, bool G32, bool O32, class Seg, class Wd>
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) void fused_adamw_kernel(const Seg a, const AdamScalars h, const Wd w)
+template <int R_T, bool G32, bool O32, class Seg, class H, class Wd>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) void fused_adamw_kernel(const Seg a, const H h, const Wd w)
 {
     // Which segment and which group of it?  When the segments are of similar length the grid is
     // two-dimensional (y = segment, x = group; surplus workgroups of shorter segments leave at
@@ -421,9 +424,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) v
     const uint32_t quad[2] = {q0, q0 + kWave};
     const bool valid[2] = {quad[0] < nquad, quad[1] < nquad};
     if ((uint64_t)(grp + 1) * kGroupQuads <= nquad)
-        fused_group<R_T, G32, O32, true>(sp, R, h, w, seg, quad, valid);
+        fused_group<R_T, G32, O32, true>(sp, R, scalars_of(h), w, seg, quad, valid);
     else
-        fused_group<R_T, G32, O32, false>(sp, R, h, w, seg, quad, valid);
+        fused_group<R_T, G32, O32, false>(sp, R, scalars_of(h), w, seg, quad, valid);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -613,8 +616,8 @@ hzp_status_t launch_reduce(bool g32, const void *const *slices, uint32_t R, uint
     return check_launch("hzp_reduce_shard");
 }
 
-template <class Seg, class Wd>
-static void launch_fused_variant(bool g32, bool o32, uint32_t R, const Seg &a, const AdamScalars &h,
+template <class Seg, class H, class Wd>
+static void launch_fused_variant(bool g32, bool o32, uint32_t R, const Seg &a, const H &h,
                                  const Wd &w, dim3 grid, hipStream_t stream)
 {
     const dim3 block(kWave);
@@ -622,7 +625,7 @@ static void launch_fused_variant(bool g32, bool o32, uint32_t R, const Seg &a, c
     // the run-time-R loop keeps two contributions in flight and needs the resident wavefronts.
     const unsigned lds = kFusedLdsBytes;
 #define HZP_FUSED_CASE(RT, G, O) \
-    hipLaunchKernelGGL((fused_adamw_kernel<RT, G, O, Seg, Wd>), grid, block, (RT) ? lds : 0u, stream, a, h, w)
+    hipLaunchKernelGGL((fused_adamw_kernel<RT, G, O, Seg, H, Wd>), grid, block, (RT) ? lds : 0u, stream, a, h, w)
     if (!g32 && !o32) {
         switch (R) {
         case 1: HZP_FUSED_CASE(1, false, false); break;
@@ -666,9 +669,9 @@ struct SegRun {
     uint64_t first, n;
 };
 
-template <class Seg>
+template <class Seg, class H>
 static hzp_status_t launch_fused_table(const hzp_plan_t *plan, bool use_wd, bool g32, bool o32, uint32_t R,
-                                       const FusedSegment *segs, size_t nseg, const AdamScalars &h,
+                                       const FusedSegment *segs, size_t nseg, const H &h,
                                        hipStream_t stream)
 {
     const DeviceTables *tab = nullptr;
@@ -750,19 +753,17 @@ static hzp_status_t launch_fused_table(const hzp_plan_t *plan, bool use_wd, bool
 }
 
 hzp_status_t launch_fused(const hzp_plan_t *plan, bool g32, bool o32, uint32_t R, const FusedSegment *segs,
-                          size_t nseg, const hzp_adamw_t &hy, hipStream_t stream)
+                          size_t nseg, const AdamScalars &h, hipStream_t stream)
 {
-    AdamScalars h;
-    h.lr = hy.lr;
-    h.beta1 = hy.beta1;
-    h.beta2 = hy.beta2;
-    h.one_minus_beta1 = 1.0f - hy.beta1;
-    h.one_minus_beta2 = 1.0f - hy.beta2;
-    h.eps = hy.eps;
-    h.weight_decay = hy.weight_decay;
-    h.grad_scale = hy.grad_scale;
-    h.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)hy.beta1, (double)hy.step)));
-    h.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)hy.beta2, (double)hy.step)));
+    if (plan->uniform_wd)
+        return launch_fused_table<SegTableWide>(plan, false, g32, o32, R, segs, nseg, h, stream);
+    return launch_fused_table<SegTableNarrow>(plan, true, g32, o32, R, segs, nseg, h, stream);
+}
+
+hzp_status_t launch_fused_dev(const hzp_plan_t *plan, bool g32, bool o32, uint32_t R, const FusedSegment *segs,
+                              size_t nseg, const AdamScalars *scalars_dev, hipStream_t stream)
+{
+    const ScalarsInMemory h{scalars_dev};
     if (plan->uniform_wd)
         return launch_fused_table<SegTableWide>(plan, false, g32, o32, R, segs, nseg, h, stream);
     return launch_fused_table<SegTableNarrow>(plan, true, g32, o32, R, segs, nseg, h, stream);

@@ -12,10 +12,15 @@ hzp_status_t launch_reduce(bool, const void *const *, uint32_t, uint64_t, float,
 {
     return no_gpu("launch_reduce");
 }
-hzp_status_t launch_fused(const hzp_plan_t *, bool, bool, uint32_t, const FusedSegment *, size_t, const hzp_adamw_t &,
+hzp_status_t launch_fused(const hzp_plan_t *, bool, bool, uint32_t, const FusedSegment *, size_t, const AdamScalars &,
                           hipStream_t)
 {
     return no_gpu("launch_fused");
+}
+hzp_status_t launch_fused_dev(const hzp_plan_t *, bool, bool, uint32_t, const FusedSegment *, size_t, const AdamScalars *,
+                              hipStream_t)
+{
+    return no_gpu("launch_fused_dev");
 }
 hzp_status_t launch_concat(const void *const *, uint32_t, uint64_t, void *, hipStream_t) { return no_gpu("launch_concat"); }
 hzp_status_t launch_concat_layers(const void *const *, uint32_t, const uint64_t *, void *const *, uint32_t, hipStream_t)

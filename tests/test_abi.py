@@ -137,6 +137,28 @@ def test_adamw_argument_errors():
     assert _status(f, p, 0, 1, 0, 0, hy, one, 1, one, one, one, [0], stream=0) == hzp.HZP_ERR_INVALID_ARG
 
 
+def test_adamw_scalars_and_the_device_form_argument_errors():
+    import numpy as np
+    hy = hzp.adamw_hyper(1e-4, 0.9, 0.95, 1e-8, 0.1, 0.125, 3)
+    f = np.array(hzp.hzp_adamw_scalars(hy), np.float32)
+    f32 = np.float32
+    b1, b2 = f32(0.9), f32(0.95)
+    want = [f32(1e-4), b1, b2, f32(1) - b1, f32(1) - b2, f32(1e-8), f32(0.1), f32(0.125),
+            f32(1.0 / (1.0 - float(b1) ** 3)), f32(1.0 / (1.0 - float(b2) ** 3)), f32(0), f32(0)]
+    assert np.array_equal(f.view(np.uint32), np.array(want, np.float32).view(np.uint32))
+    assert abs(float(f[8]) - 1.0 / 0.271) < 1e-5 and abs(float(f[9]) - 1.0 / 0.142625) < 1e-5   # closed forms at step 3
+    assert _status(hzp.hzp_adamw_scalars, hzp.adamw_hyper(1e-4, 0.9, 0.95, 1e-8, 0.1, 0.5, 0)) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(hzp.hzp_adamw_scalars, None) == hzp.HZP_ERR_INVALID_ARG
+    p = _plan()
+    g = hzp.hzp_adamw_shard_dev
+    one = [FAKE]
+    assert _status(g, p, 0, 1, 0, 0, 0, one, 1, one, one, one, one, stream=0) == hzp.HZP_ERR_INVALID_ARG      # NULL scalars
+    assert _status(g, p, 0, 1, 0, 0, FAKE + 4, one, 1, one, one, one, one, stream=0) == hzp.HZP_ERR_ALIGN
+    assert _status(g, p, 0, 0, 0, 0, FAKE, one, 1, one, one, one, one, stream=0) == hzp.HZP_ERR_INVALID_ARG   # empty range
+    assert _status(g, p, 0, 1, 0, 0, FAKE, one, 1, [0], one, one, one, stream=0) == hzp.HZP_ERR_INVALID_ARG
+    assert _status(g, p, 0, 1, 0, 0, FAKE, one * 33, 33, one, one, one, one, stream=0) == hzp.HZP_ERR_UNSUPPORTED
+
+
 def test_arena_tune_argument_errors_before_any_gpu_call():
     p = _plan()
     f = p.arena_tune
