@@ -210,6 +210,8 @@ class Workload:
                           for jj in range(self.z3)]
                 bucket = piece("bucket", self.p_total, bf16, b.base, b.padded)
             self.keep.append((grads, p, m, v, out, owners, shard3, shards, bucket))
+            if (l + 1) % 8 == 0:        # a sign of life on stderr: building takes minutes under a counter-collecting profiler
+                print("bench: %s: buffers of %d of %d layers filled" % (cfg["name"], l + 1, n_layers), file=sys.stderr, flush=True)
             g_ptrs += grads
             p_ptrs.append(p); m_ptrs.append(m); v_ptrs.append(v); o_ptrs.append(out)
             self.l1_args.append((l, hzp.ptr_array(owners), shard3.data_ptr()))
@@ -840,7 +842,7 @@ def time_workload(idx, args, torch, np, hzp, hzp_inputs, steps, warmup, keep=Fal
                                           w.n_layers, "concat_l3_%s" % cfg["name"], ph[:, 2])
     # the launch-bound workloads also as one captured step replayed (context; the timed steps are issued call by call)
     graph = None
-    if cfg["name"] in ("tiny", "irregular") and phases == {"fused", "gather1", "gather3"}:
+    if cfg["name"] in ("tiny", "irregular") and phases == {"fused", "gather1", "gather3"} and steps >= 10:
         graph = graph_probe(w, hzp, torch, stream, phases, max(steps, 20), warmup)
     out = {
         "graph_replay": graph,
