@@ -310,8 +310,15 @@ int main()
             HZP(hzp_plan_arena_slice(plan, HZP_CLASS_BF16, R, HZP_GRAD_DEFAULT, variant, HZP_STREAM_PARAM_OUT, 0, l, &off, &nb));
             ao[l] = arena + off;
         }
-        HZP(hzp_adamw_shard(plan, 0, 2, HZP_CLASS_BF16, rank, &hyper, ag, R, ap, am, av, ao, stream));
+        // ... through the form that reads the step's scalars from device memory
+        hzp_adamw_scalars_t hscal;
+        HZP(hzp_adamw_scalars(&hyper, &hscal));
+        hzp_adamw_scalars_t *dscal = nullptr;
+        HIP(hipMalloc((void **)&dscal, sizeof hscal));
+        HIP(hipMemcpy(dscal, &hscal, sizeof hscal, hipMemcpyHostToDevice));
+        HZP(hzp_adamw_shard_dev(plan, 0, 2, HZP_CLASS_BF16, rank, dscal, ag, R, ap, am, av, ao, stream));
         HIP(hipStreamSynchronize(stream));
+        HIP(hipFree(dscal));
         for (uint32_t l = 0; l < 2; ++l) {
             std::vector<float> got(b[l].s1), first(b[l].s1), gotv(b[l].s1), firstv(b[l].s1);
             if (!to_host(got, ap[l]) || !to_host(first, dp[l]) || !to_host(gotv, av[l]) || !to_host(firstv, dv[l])) return 2;
@@ -328,6 +335,6 @@ int main()
         printf("selftest: %d mismatches\n", bad);
         return 1;
     }
-    printf("selftest ok: fused update of 2 layers (rank %u: j=%u k=%u i=%u), gathers, unpack, reduction, arena and tuner\n", rank, j, k, i);
+    printf("selftest ok: fused update of 2 layers (rank %u: j=%u k=%u i=%u), gathers, unpack, reduction, arena and tuner, scalars in device memory\n", rank, j, k, i);
     return 0;
 }
